@@ -1,0 +1,453 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test names what it pins and what fixes the expected value: a library
+routine on the CPU in fp64 (torch LSTM / scaled_dot_product_attention / gelu /
+topk), a closed form, an invariant of the paper's definitions, or a brute-force
+recomputation in a deliberately different formulation.  The paper prints no
+worked numerical example of this path, so there is no golden fixture from it.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_21354_amd import synth
+
+TINY = synth.Config(90, "tiny", "f32", L=2, B=2, H=3, d=8, T=48, C=4, k=3, W=10, d_sum=12, d_g=6,
+                    Tq=2)
+
+
+def _f64(x):
+    return torch.as_tensor(x).to(torch.float64)
+
+
+def _inputs(cfg):
+    t = synth.make_inputs(cfg, "cpu")
+    return t
+
+
+def _mlp_w(t, kv):
+    return tuple(t[n + kv] for n in ("W1", "b1", "W2", "b2"))
+
+
+def _lstm_w(t):
+    return tuple(t[n] for n in ("W_ih", "W_hh", "b_ih", "b_hh", "w_s", "b_s"))
+
+
+# ---------------------------------------------------------------- rounding
+
+def test_bf16_rounding_is_nearest_even_and_single(oracle):
+    r = oracle.bf16_round
+    assert r(1.0) == 0x3F80
+    assert r(-2.0) == 0xC000
+    assert r(1.0 + 2.0 ** -8) == 0x3F80            # tie -> even
+    assert r(1.0 + 3 * 2.0 ** -8) == 0x3F82        # tie -> even (up)
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -30) == 0x3F81   # above the tie: a double->float->bf16 path gets 0x3F80
+    assert r(0.0) == 0 and r(-0.0) == 0x8000
+    assert r(float("inf")) == 0x7F80 and r(3.4e38) == 0x7F80   # overflow of the largest finite
+    assert r(2.0 ** -133) == 0x0001 and r(2.0 ** -134) == 0x0000  # subnormal quantum, tie -> even
+    assert (r(float("nan")) & 0x7FC0) == 0x7FC0
+    # values exactly representable in fp32: torch's conversion is then a single rounding too
+    g = torch.Generator().manual_seed(1)
+    x = torch.randn(2000, generator=g, dtype=torch.float32) * 10
+    want = x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([r(float(v)) for v in x], np.uint16)
+    assert (want == got).all()
+
+
+def test_gelu_is_the_erf_form(oracle):
+    xs = np.linspace(-6, 6, 241)
+    want = torch.nn.functional.gelu(torch.tensor(xs, dtype=torch.float64)).numpy()
+    got = np.array([oracle.gelu(x) for x in xs])
+    assert np.abs(got - want).max() < 1e-15
+    assert oracle.gelu(0.0) == 0.0 and abs(oracle.gelu(1.0) - 0.8413447460685429) < 1e-15
+
+
+# -------------------------------------------------------------------- pool
+
+def test_pool_matches_library_mlp_on_the_chunk_mean(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP,
+                                   _mlp_w(t, "K"), _mlp_w(t, "V"), 0, cfg.N)
+    for X, Y, kv in ((t["K"], Kbar, "K"), (t["V"], Vbar, "V")):
+        x = _f64(X).view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d).mean(dim=4)
+        for l in range(cfg.L):
+            W1, b1, W2, b2 = (_f64(w[l]) for w in _mlp_w(t, kv))
+            z = torch.nn.functional.linear(x[l], W1, b1)
+            y = torch.nn.functional.linear(torch.nn.functional.gelu(z), W2, b2)
+            assert np.abs(Y[l] - y.to(torch.float32).numpy()).max() <= 1e-6
+
+
+def test_pool_closed_forms(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    wK, wV = _mlp_w(t, "K"), _mlp_w(t, "V")
+    ref = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP, wK, wV,
+                            0, cfg.N)
+    # permuting the tokens inside each chunk changes nothing up to summation order
+    K5 = t["K"].view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d)
+    perm = torch.tensor([2, 0, 3, 1])
+    Kp = K5[:, :, :, :, perm].reshape(t["K"].shape).contiguous()
+    got = oracle.chunk_pool(Kp, t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP, wK, wV, 0,
+                            cfg.N)
+    assert np.abs(got[0] - ref[0]).max() < 1e-6 and (got[1] == ref[1]).all()
+    # a chunk whose tokens are all equal to x pools to MLP(x), whatever C
+    x = t["K"][:, :, :, :1]
+    for C in (1, 3, 8):
+        Kc = x.expand(-1, -1, -1, C, -1).contiguous()
+        a = oracle.chunk_pool(Kc, Kc, C, C, 1, cfg.d_sum, oracle.POOL_MLP, wK, wK, 0, 1)
+        b = oracle.chunk_pool(x.contiguous(), x.contiguous(), 1, 1, 1, cfg.d_sum, oracle.POOL_MLP,
+                              wK, wK, 0, 1)
+        assert np.abs(a[0] - b[0]).max() < 1e-6 and (a[0] == a[1]).all()
+    # MEAN mode is the arithmetic mean, rounded once
+    m = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MEAN, None,
+                          None, 0, cfg.N)
+    want = _f64(t["V"]).view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d).mean(4).to(torch.float32)
+    assert np.abs(m[1] - want.numpy()).max() <= 1e-7
+    # only rows [c0, c1) are written; a trailing partial chunk is never pooled
+    part = oracle.chunk_pool(t["K"], t["V"], cfg.T - 1, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP,
+                             wK, wV, 2, cfg.N - 1)
+    assert (part[0][..., 2:cfg.N - 1, :] == ref[0][..., 2:cfg.N - 1, :]).all()
+    assert (part[0][..., :2, :] == 0).all() and (part[0][..., cfg.N - 1:, :] == 0).all()
+    with pytest.raises(ValueError):
+        oracle.chunk_pool(t["K"], t["V"], cfg.T - 1, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP, wK,
+                          wV, 0, cfg.N)
+
+
+def test_pool_bf16_storage_rounds_once(oracle):
+    cfg = TINY.replace(dtype="bf16", number=91)
+    t = _inputs(cfg)
+    Kbar, _ = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MEAN,
+                                None, None, 0, cfg.N)
+    assert Kbar.dtype == np.uint16
+    mean = _f64(t["K"]).view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d).mean(4)
+    # sums of 4 bf16 values are exact in fp32, so torch's fp32->bf16 is the single rounding
+    want = mean.to(torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (Kbar == want).all()
+
+
+# -------------------------------------------------------------------- gate
+
+def _torch_lstm(cfg, t, l, x):
+    """fp64 library LSTM + linear head with layer l's weights; x [S, N, 2d]."""
+    lstm = torch.nn.LSTM(2 * cfg.d, cfg.d_g, batch_first=True, dtype=torch.float64)
+    with torch.no_grad():
+        lstm.weight_ih_l0.copy_(_f64(t["W_ih"][l]))
+        lstm.weight_hh_l0.copy_(_f64(t["W_hh"][l]))
+        lstm.bias_ih_l0.copy_(_f64(t["b_ih"][l]))
+        lstm.bias_hh_l0.copy_(_f64(t["b_hh"][l]))
+        hs, (hn, cn) = lstm(x)
+        u = hs @ _f64(t["w_s"][l]) + _f64(t["b_s"][l])
+    return hs, hn[0], cn[0], u
+
+
+def test_lstm_gate_matches_library_lstm(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP,
+                                   _mlp_w(t, "K"), _mlp_w(t, "V"), 0, cfg.N)
+    h, c, util, gate = oracle.lstm_gate(Kbar, Vbar, _lstm_w(t), 0, cfg.N)
+    for l in range(cfg.L):
+        x = torch.cat([_f64(Kbar[l]), _f64(Vbar[l])], dim=-1).view(cfg.B * cfg.H, cfg.N, 2 * cfg.d)
+        _, hn, cn, u = _torch_lstm(cfg, t, l, x)
+        assert np.abs(h[l].reshape(-1, cfg.d_g) - hn.numpy()).max() < 2e-6
+        assert np.abs(c[l].reshape(-1, cfg.d_g) - cn.numpy()).max() < 2e-6
+        assert np.abs(util[l].reshape(-1, cfg.N) - u.numpy()).max() < 2e-6
+        assert np.abs(gate[l].reshape(-1, cfg.N) - torch.sigmoid(u).numpy()).max() < 2e-6
+    assert (gate >= 0).all() and (gate <= 1).all()
+
+
+def test_lstm_gate_closed_forms_and_resumption(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP,
+                                   _mlp_w(t, "K"), _mlp_w(t, "V"), 0, cfg.N)
+    w = list(_lstm_w(t))
+    zero = [torch.zeros_like(x) for x in w[:4]] + w[4:]
+    h, c, util, gate = oracle.lstm_gate(Kbar, Vbar, zero, 0, cfg.N)
+    # all-zero cell weights: i=f=o=1/2, g=0 -> c=h=0, u=b_s, s=sigmoid(b_s)
+    assert (h == 0).all() and (c == 0).all()
+    for l in range(cfg.L):
+        bs = float(t["b_s"][l])
+        assert (util[l] == np.float32(bs)).all()
+        assert np.abs(gate[l] - 1 / (1 + math.exp(-bs))).max() < 1e-7
+    # cutting the run into calls that carry (h, c) gives the same bits as one call
+    full = oracle.lstm_gate(Kbar, Vbar, w, 0, cfg.N)
+    hh = cc = uu = gg = None
+    for a, b in ((0, 1), (1, 5), (5, 5), (5, cfg.N)):
+        hh, cc, uu, gg = oracle.lstm_gate(Kbar, Vbar, w, a, b, hh, cc, uu, gg)
+    for x, y in zip(full, (hh, cc, uu, gg)):
+        assert (x == y).all()
+    # the score at step t does not depend on later chunks (causal scan)
+    Kb2 = Kbar.copy()
+    Kb2[..., 7:, :] += 1.0
+    _, _, u2, _ = oracle.lstm_gate(Kb2, Vbar, w, 0, cfg.N)
+    assert (u2[..., :7] == full[2][..., :7]).all() and (u2[..., 7:] != full[2][..., 7:]).any()
+    # K comes first in the concatenated input: swapping K and V summaries changes the scores,
+    # swapping them together with the two halves of W_ih does not
+    w_sw = list(w)
+    w_sw[0] = torch.cat([t["W_ih"][..., cfg.d:], t["W_ih"][..., :cfg.d]], dim=-1).contiguous()
+    _, _, u3, _ = oracle.lstm_gate(Vbar, Kbar, w_sw, 0, cfg.N)
+    assert np.abs(u3 - full[2]).max() < 1e-6
+    _, _, u4, _ = oracle.lstm_gate(Vbar, Kbar, w, 0, cfg.N)
+    assert np.abs(u4 - full[2]).max() > 1e-3
+
+
+# ------------------------------------------------------------------ select
+
+def test_select_topk_invariants_and_library_topk(oracle):
+    rng = np.random.default_rng(5)
+    S, N_cap, C = 7, 40, 4
+    util = rng.standard_normal((S, N_cap)).astype(np.float32)
+    for T, W, k in ((160, 16, 9), (160, 0, 40), (160, 158, 3), (103, 17, 5), (12, 16, 4),
+                    (160, 16, 0)):
+        n_cand = max(0, T - W) // C
+        idx, count = oracle.select_topk(util, T, C, W, k, max(k, 1))
+        keep = min(k, n_cand)
+        assert (count == keep).all()
+        for s in range(S):
+            got = idx[s, :keep]
+            assert (np.diff(got) > 0).all() and (got >= 0).all() and (got < n_cand).all()
+            if keep:
+                top = torch.topk(torch.tensor(util[s, :n_cand]), keep).indices.sort().values
+                assert (got == top.numpy()).all()          # distinct values: unique answer
+            dropped = np.setdiff1d(np.arange(n_cand), got)
+            if keep and len(dropped):
+                assert util[s, dropped].max() <= util[s, got].min()
+            assert (idx[s, keep:] == -1).all()             # tail left untouched
+
+
+def test_select_ties_go_to_the_lower_index_and_nan_is_minus_infinity(oracle):
+    util = np.zeros((1, 16), np.float32)
+    idx, count = oracle.select_topk(util, 64, 4, 0, 5, 5)
+    assert count[0] == 5 and (idx[0] == np.arange(5)).all()
+    util[0, [3, 9, 12]] = 1.0
+    util[0, 4] = np.nan
+    util[0, 5] = -np.inf
+    idx, _ = oracle.select_topk(util, 64, 4, 0, 6, 6)
+    assert idx[0].tolist() == [0, 1, 2, 3, 9, 12]
+    idx, _ = oracle.select_topk(util, 64, 4, 0, 15, 16)
+    assert idx[0, :15].tolist() == [0, 1, 2, 3, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15]  # -inf(5) after nan(4)
+    with pytest.raises(ValueError):
+        oracle.select_topk(util, 64, 4, 0, 6, 5)           # k_cap < kept count
+
+
+def test_select_threshold_is_the_literal_rule(oracle):
+    rng = np.random.default_rng(6)
+    gate = rng.random((5, 30)).astype(np.float32)
+    idx, count = oracle.select_threshold(gate, 120, 4, 8, 0.5, 30)
+    n_cand = (120 - 8) // 4
+    for s in range(5):
+        want = np.nonzero(gate[s, :n_cand] >= np.float32(0.5))[0]
+        assert count[s] == len(want) and (idx[s, :len(want)] == want).all()
+
+
+# --------------------------------------------------------------- attention
+
+def test_dense_attention_matches_library_sdpa(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    O, P = oracle.dense_attention(t["Q"], t["K"], t["V"], cfg.T, want_probs=True)
+    want = torch.nn.functional.scaled_dot_product_attention(_f64(t["Q"]), _f64(t["K"]),
+                                                            _f64(t["V"]))
+    assert np.abs(O - want.to(torch.float32).numpy()).max() <= 1e-6
+    assert np.abs(P.sum(-1) - 1).max() < 1e-12 and (P >= 0).all()
+    # a shorter T only sees the first T tokens
+    O2 = oracle.dense_attention(t["Q"], t["K"], t["V"], 17)
+    want2 = torch.nn.functional.scaled_dot_product_attention(
+        _f64(t["Q"]), _f64(t["K"][..., :17, :]), _f64(t["V"][..., :17, :]))
+    assert np.abs(O2 - want2.to(torch.float32).numpy()).max() <= 1e-6
+
+
+def test_identity_pool_keep_all_reduces_to_full_attention(oracle):
+    """C = 1, mean pool, keep every candidate: the gated step IS Eq. 1 over the cache."""
+    cfg = TINY.replace(C=1, W=7, k=10 ** 6)
+    t = _inputs(cfg)
+    for dtype in ("f32", "bf16"):
+        c2 = cfg.replace(dtype=dtype)
+        t = _inputs(c2)
+        Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], c2.T, 1, c2.T, c2.d_sum, oracle.POOL_MEAN,
+                                       None, None, 0, c2.T)
+        assert (Kbar == oracle.to_np(t["K"])).all()
+        util = np.random.default_rng(0).standard_normal((c2.L, c2.B, c2.H, c2.T)).astype(np.float32)
+        idx, count = oracle.select_topk(util, c2.T, 1, c2.W, c2.k, c2.T)
+        assert (count == c2.T - c2.W).all()
+        O = oracle.gated_attention(t["Q"], t["K"], t["V"], Kbar, Vbar, idx, count, c2.T, 1, c2.W)
+        D = oracle.dense_attention(t["Q"], t["K"], t["V"], c2.T)
+        assert (O == D).all()          # same rows in the same order: same bits
+
+
+def test_softmax_weights_and_convexity(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    O, P = oracle.gated_attention(t["Q"], t["K"], t["V"], r["Kbar"], r["Vbar"], r["idx"],
+                                  r["count"], cfg.T, cfg.C, cfg.W, want_probs=True)
+    n = cfg.k + cfg.T - cfg.N_cand * cfg.C
+    assert P.shape[-1] == n
+    assert np.abs(P.sum(-1) - 1).max() < 1e-12 and (P >= 0).all()
+    # each output coordinate is a convex combination of the attended values
+    V = _f64(t["V"]).numpy()
+    for s in np.ndindex(cfg.L, cfg.B, cfg.H):
+        rows = np.concatenate([r["Vbar"][s][r["idx"][s][:r["count"][s]]].astype(np.float64),
+                               V[s][cfg.N_cand * cfg.C:cfg.T]])
+        assert rows.shape[0] == n
+        assert (O[s] <= rows.max(0) + 1e-6).all() and (O[s] >= rows.min(0) - 1e-6).all()
+        assert np.abs(P[s] @ rows - O[s]).max() < 1e-6
+
+
+def test_zero_query_gives_the_mean_and_one_hot_picks_the_row(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    Q0 = torch.zeros_like(t["Q"])
+    O = oracle.gated_attention(Q0, t["K"], t["V"], r["Kbar"], r["Vbar"], r["idx"], r["count"],
+                               cfg.T, cfg.C, cfg.W)
+    V = _f64(t["V"]).numpy()
+    win0 = cfg.N_cand * cfg.C
+    for s in np.ndindex(cfg.L, cfg.B, cfg.H):
+        rows = np.concatenate([r["Vbar"][s][r["idx"][s]].astype(np.float64), V[s][win0:cfg.T]])
+        assert np.abs(O[s] - rows.mean(0)).max() < 1e-6
+    # one-hot: make one key dominate; the output must be that row's value.  Done for a kept
+    # summary (through idx) and for a raw window token.
+    s = (1, 0, 2)
+    Kbar = r["Kbar"].copy()
+    Kraw = t["K"].clone()
+    q = _f64(t["Q"])[s][0].numpy()
+    j = 1                                     # second kept chunk
+    cidx = int(r["idx"][s][j])
+    Kbar[s][cidx] = (q / np.linalg.norm(q) * 300).astype(np.float32)
+    O1 = oracle.gated_attention(t["Q"], Kraw, t["V"], Kbar, r["Vbar"], r["idx"], r["count"], cfg.T,
+                                cfg.C, cfg.W)
+    assert np.abs(O1[s][0] - r["Vbar"][s][cidx]).max() < 1e-6
+    tok = win0 + 3
+    Kraw[s][tok] = torch.tensor(q / np.linalg.norm(q) * 300, dtype=torch.float32)
+    O2 = oracle.gated_attention(t["Q"], Kraw, t["V"], r["Kbar"], r["Vbar"], r["idx"], r["count"],
+                                cfg.T, cfg.C, cfg.W)
+    assert np.abs(O2[s][0] - t["V"][s][tok].numpy()).max() < 1e-6
+    # tokens of dropped chunks and tokens before the window are invisible
+    Kraw2, Vraw2 = t["K"].clone(), t["V"].clone()
+    Kraw2[..., :win0, :] = 99.0
+    Vraw2[..., :win0, :] = -99.0
+    O3 = oracle.gated_attention(t["Q"], Kraw2, Vraw2, r["Kbar"], r["Vbar"], r["idx"], r["count"],
+                                cfg.T, cfg.C, cfg.W)
+    assert (O3 == r["O"]).all()
+
+
+# ----------------------------------------------------- brute force, whole chain
+
+def _brute_chain(cfg, t, s):
+    """The whole step for one (l,b,h), written differently on purpose: explicit
+    matrices, naive softmax without max shift, python sort with a key."""
+    l = s[0]
+    f = lambda name: _f64(t[name][l]).numpy()
+    K, V, Q = (_f64(t[n][s]).numpy() for n in ("K", "V", "Q"))
+    erf = np.vectorize(math.erf)
+    N = cfg.T // cfg.C
+    xs = []
+    for X, kv in ((K, "K"), (V, "V")):
+        m = np.stack([X[c * cfg.C:(c + 1) * cfg.C].sum(0) / cfg.C for c in range(N)])
+        z = m @ f("W1" + kv).T + f("b1" + kv)
+        a = z * 0.5 * (1 + erf(z / math.sqrt(2)))
+        y = a @ f("W2" + kv).T + f("b2" + kv)
+        xs.append(y.astype(np.float32).astype(np.float64))      # stored once as fp32
+    Kbar, Vbar = xs
+    Wcat = np.concatenate([f("W_ih"), f("W_hh")], axis=1)
+    bias = f("b_ih") + f("b_hh")
+    h = np.zeros(cfg.d_g)
+    c = np.zeros(cfg.d_g)
+    u = []
+    sg = lambda v: 1 / (1 + np.exp(-v))
+    for n in range(N):
+        pre = Wcat @ np.concatenate([Kbar[n], Vbar[n], h]) + bias
+        i, fg, g, o = np.split(pre, 4)
+        c = (sg(fg) * c + sg(i) * np.tanh(g)).astype(np.float32).astype(np.float64)
+        h = (sg(o) * np.tanh(c)).astype(np.float32).astype(np.float64)
+        u.append(np.float32(f("w_s") @ h + float(t["b_s"][l])))
+    n_cand = max(0, cfg.T - cfg.W) // cfg.C
+    order = sorted(range(n_cand), key=lambda j: (-u[j], j))[:min(cfg.k, n_cand)]
+    kept = sorted(order)
+    keys = np.concatenate([Kbar[kept].reshape(-1, cfg.d), K[n_cand * cfg.C:cfg.T]])
+    vals = np.concatenate([Vbar[kept].reshape(-1, cfg.d), V[n_cand * cfg.C:cfg.T]])
+    e = np.exp(Q @ keys.T / math.sqrt(cfg.d))
+    return kept, np.array(u), (e / e.sum(-1, keepdims=True)) @ vals
+
+
+@pytest.mark.parametrize("cfg", [
+    synth.Config(92, "bf1", "f32", L=1, B=1, H=1, d=4, T=16, C=4, k=2, W=4, d_sum=5, d_g=3, Tq=1),
+    synth.Config(93, "bf2", "f32", L=2, B=1, H=2, d=4, T=15, C=2, k=3, W=3, d_sum=3, d_g=4, Tq=2),
+    synth.Config(94, "bf3", "f32", L=1, B=2, H=1, d=4, T=9, C=3, k=5, W=2, d_sum=4, d_g=2, Tq=1),
+])
+def test_brute_force_chain_on_tiny_inputs(oracle, cfg):
+    t = _inputs(cfg)
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    for s in np.ndindex(cfg.L, cfg.B, cfg.H):
+        kept, u, O = _brute_chain(cfg, t, s)
+        assert r["idx"][s][:r["count"][s]].tolist() == kept
+        assert np.abs(r["util"][s][:len(u)] - u).max() < 1e-6
+        assert np.abs(r["O"][s] - O).max() < 1e-6
+
+
+# ------------------------------------------------------------ streaming, edges
+
+def test_streaming_equals_cold_recompute_at_every_step(oracle):
+    cfg = synth.Config(95, "stream", "bf16", L=1, B=2, H=2, d=8, T=96, C=4, k=5, W=8, d_sum=8,
+                       d_g=8, Tq=1, steps=8, frame=12, decode_per_step=2)
+    t = _inputs(cfg)
+    Qs = synth.make_stream_queries(cfg)
+    inc = oracle.stream(Qs, t["K"], t["V"], t, cfg.frame, cfg.steps, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    for s, st in enumerate(inc):
+        T = (s + 1) * cfg.frame
+        for i in range(cfg.decode_per_step):
+            r = oracle.cold_step(Qs[s, i], t["K"], t["V"], t, T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+            assert (r["idx"] == st["idx"]).all() and (r["count"] == st["count"]).all()
+            assert (r["O"] == st["O"][i]).all()
+        assert (r["h"] == st["h"]).all() and (r["c"] == st["c"]).all()
+        assert st["count"].max() == min(cfg.k, max(0, T - cfg.W) // cfg.C)
+
+
+def test_edge_cases(oracle):
+    cfg = TINY
+    t = _inputs(cfg)
+    # T < W: no candidate, attention is over the raw tokens [0, T) only == dense over T
+    for T, W, k in ((9, 10, 3), (cfg.T, cfg.T, 3), (cfg.T, cfg.T - 3, 3), (cfg.T, cfg.W, 0)):
+        r = oracle.cold_step(t["Q"], t["K"], t["V"], t, T, cfg.C, W, k, cfg.d_sum, k_cap=3)
+        n_cand = max(0, T - W) // cfg.C
+        assert (r["count"] == min(k, n_cand)).all()
+        if min(k, n_cand) == 0:
+            Kz, Vz = t["K"].clone(), t["V"].clone()
+            Kz[..., :n_cand * cfg.C, :] = 0
+            D = oracle.dense_attention(t["Q"], t["K"][..., n_cand * cfg.C:, :].contiguous(),
+                                       t["V"][..., n_cand * cfg.C:, :].contiguous(),
+                                       T - n_cand * cfg.C)
+            assert (r["O"] == D).all()
+    # k > N_cand keeps every candidate
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, 1000, cfg.d_sum,
+                         k_cap=cfg.N_cand)
+    assert (r["count"] == cfg.N_cand).all()
+    assert (r["idx"] == np.arange(cfg.N_cand)).all()
+    # T not a multiple of C: the raw window grows back to the chunk boundary; every token is
+    # in exactly one of {candidate chunk, raw window}
+    T, W = 47, 10
+    n_cand = (T - W) // cfg.C
+    O, P = oracle.gated_attention(t["Q"], t["K"], t["V"], r["Kbar"], r["Vbar"],
+                                  np.arange(n_cand, dtype=np.int32)[None, None, None].repeat(
+                                      cfg.L, 0).repeat(cfg.B, 1).repeat(cfg.H, 2),
+                                  np.full((cfg.L, cfg.B, cfg.H), n_cand, np.int32), T, cfg.C, W,
+                                  want_probs=True)
+    assert P.shape[-1] == n_cand + (T - n_cand * cfg.C)
+    assert W <= T - n_cand * cfg.C < W + cfg.C
+    # Tq = 0 and an empty attended set are well defined
+    Oe = oracle.dense_attention(t["Q"], t["K"], t["V"], 0)
+    assert (Oe == 0).all()
+
+
+def test_config1_whole_chain_runs_in_seconds(oracle):
+    cfg = synth.CONFIGS[1]
+    t = _inputs(cfg)
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    assert cfg.N == 64 and cfg.N_cand == 60
+    assert (r["count"] == cfg.k).all()                     # kept-chunk count equals k
+    assert np.isfinite(r["O"]).all() and r["O"].shape == (1, 1, 4, 1, 64)
