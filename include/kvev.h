@@ -1,0 +1,161 @@
+/*
+ * kvev — RNN-gated chunked KV-cache decode attention for AMD MI355X (gfx950).
+ *
+ * C ABI of the per-layer decode step of KV-Efficient VLA (arXiv 2509.21354):
+ * the history KV cache is cut into fixed-length chunks, each chunk is pooled
+ * into one summary key/value by a small MLP, an LSTM scores the summaries, the
+ * top-k chunks are kept, and the new queries attend over the kept summaries
+ * plus the raw recent window.  A full-cache attention entry point serves as
+ * the baseline the method is compared with.
+ *
+ * Conventions (all entry points)
+ *   - Every function returns an int status (KVEV_OK = 0) and never throws.
+ *   - Arguments are validated on the host before any HIP call; a failed
+ *     validation enqueues nothing.
+ *   - Work is enqueued asynchronously on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream).  The library never allocates, frees
+ *     or synchronises: the caller owns every buffer, including scratch, whose
+ *     size kvev_workspace_bytes() reports.
+ *   - `kvev_shape`, `kvev_mlp_w`, `kvev_lstm_w` are HOST structs; every other
+ *     pointer is a DEVICE pointer, 16-byte aligned, row-major, contiguous.
+ *   - Results are deterministic: same inputs, same bits (no float atomics).
+ *
+ * Symbols follow the paper: C chunk length, W raw recent window, d_sum
+ * aggregator hidden width, d_g gate hidden width, n' = W + M attended rows.
+ * Derived: N = floor(T/C) completed chunks, N_cand = floor(max(0,T-W)/C)
+ * candidate chunks (those that lie wholly outside the window),
+ * win0 = N_cand*C first raw-window token.
+ */
+#ifndef KVEV_H
+#define KVEV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { KVEV_OK = 0, KVEV_ERR_INVALID_ARG = 1, KVEV_ERR_UNSUPPORTED = 2, KVEV_ERR_WORKSPACE = 3,
+       KVEV_ERR_HIP = 4 };
+enum { KVEV_F32 = 0, KVEV_BF16 = 1 };           /* storage type of Q/K/V, summaries, weights */
+enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1 };
+enum { KVEV_SELECT_TOPK = 0, KVEV_SELECT_THRESHOLD = 1 };
+enum { KVEV_OP_CHUNK_POOL = 0, KVEV_OP_LSTM_GATE = 1, KVEV_OP_SELECT = 2,
+       KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4 };
+
+/* Problem shape.  L layers are batched in one call; a "sequence" is one
+ * (layer, batch row, head) triple, S = L*B*H of them, each independent.
+ * T tokens are valid out of T_cap allocated per sequence; N_cap summary rows
+ * are allocated per sequence (N_cap >= floor(T/C)).
+ * Supported: d in {64, 128}; dtype KVEV_F32 or KVEV_BF16; any C, W, d_sum, d_g
+ * >= 1 (bf16 with d_sum % 32 == 0 and d_g % 64 == 0 takes the MFMA kernels). */
+typedef struct {
+    int32_t L, B, H, d;
+    int32_t T, T_cap;
+    int32_t C, N_cap;
+    int32_t W;
+    int32_t d_sum, d_g;
+    int32_t dtype;
+} kvev_shape;
+
+/* Aggregator MLP of Eq. 2, one set per layer (shared by batch rows and heads),
+ * in the storage dtype, row-major [out][in]:
+ * W1 [L,d_sum,d]  b1 [L,d_sum]  W2 [L,d,d_sum]  b2 [L,d]. */
+typedef struct { const void *W1, *b1, *W2, *b2; } kvev_mlp_w;
+
+/* LSTM gate of Eq. 3, one set per layer, storage dtype, gate row blocks in
+ * the order i, f, g, o:
+ * W_ih [L,4d_g,2d] (columns: Kbar first, then Vbar)  W_hh [L,4d_g,d_g]
+ * b_ih, b_hh [L,4d_g]   scalar utility head  w_s [L,d_g]  b_s [L]. */
+typedef struct { const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s; } kvev_lstm_w;
+
+/* Eq. 2 (chunk aggregation; section 3.3 "each completed chunk is aggregated
+ * ... by a 2-layer MLP").  For every sequence and every chunk c in
+ * [chunk_begin, chunk_end):  xbar = mean of the chunk's C keys;
+ * Kbar[c] = W2 * GELU(W1 * xbar + b1) + b2 with the K weights (exact erf GELU),
+ * the same for V with the V weights; KVEV_POOL_MEAN stores xbar itself (wK, wV
+ * may then be NULL).  Mean, both layers and GELU are evaluated in fp32-grade
+ * arithmetic; each summary element is rounded once to the storage dtype.
+ *   K, V        [L,B,H,T_cap,d]   read: tokens [chunk_begin*C, chunk_end*C)
+ *   Kbar, Vbar  [L,B,H,N_cap,d]   written: rows [chunk_begin, chunk_end) only
+ * Needs 0 <= chunk_begin <= chunk_end <= floor(T/C) <= N_cap.  Workspace: none
+ * (ws may be NULL).  Errors: INVALID_ARG for null/misaligned pointers or a bad
+ * range; UNSUPPORTED for d, dtype or pool_mode outside the lists above. */
+int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int pool_mode,
+                    const kvev_mlp_w *wK, const kvev_mlp_w *wV, int chunk_begin, int chunk_end,
+                    void *Kbar, void *Vbar, void *ws, size_t ws_bytes, void *stream);
+
+/* Eq. 3 (recurrent gate).  For every sequence, for t in [chunk_begin,
+ * chunk_end) in order: x_t = [Kbar_t ; Vbar_t]; standard LSTM cell
+ *   (i,f,g,o) = W_ih x_t + b_ih + W_hh h_{t-1} + b_hh;  c_t = s(f) c_{t-1} + s(i) tanh(g);
+ *   h_t = s(o) tanh(c_t);   util_t = w_s . h_t + b_s;   gate_t = s(util_t) in [0,1].
+ * State, pre-activations and scores are fp32.
+ *   h, c        [L,B,H,d_g] fp32, in/out: the caller zeroes them before the
+ *               first call of a stream (chunk_begin == 0) and passes them back
+ *               unchanged to continue it
+ *   util, gate  [L,B,H,N_cap] fp32, entries [chunk_begin, chunk_end) written
+ * Needs 0 <= chunk_begin <= chunk_end <= N_cap.  Workspace: see
+ * kvev_workspace_bytes (fp32 input projections of a block of steps); any size
+ * from one step's worth up is accepted, smaller blocks mean more launches.
+ * Errors: INVALID_ARG, UNSUPPORTED as above; WORKSPACE if ws is too small. */
+int kvev_lstm_gate(const kvev_shape *shape, const void *Kbar, const void *Vbar,
+                   const kvev_lstm_w *w, int chunk_begin, int chunk_end, float *h, float *c,
+                   float *util, float *gate, void *ws, size_t ws_bytes, void *stream);
+
+/* Retention.  Candidates are chunks 0 .. N_cand-1.
+ * KVEV_SELECT_TOPK: keep the min(k, N_cand) candidates of largest util, ties
+ * going to the lower index, a NaN counting as minus infinity (`gate`, `tau`
+ * ignored; gate may be NULL).  KVEV_SELECT_THRESHOLD (the literal rule of
+ * section 3.2): keep candidate c iff gate[c] >= tau (`k` ignored, util may be
+ * NULL; needs k_cap >= N_cand).
+ *   idx    [L,B,H,k_cap] int32: kept chunk indices, ascending, in entries
+ *          [0, count); the rest is left untouched
+ *   count  [L,B,H] int32
+ * Integer output is exact.  Needs k >= 0, k_cap >= min(k, N_cand),
+ * N_cand <= N_cap and N_cand <= 16384.  No workspace. */
+int kvev_select(const kvev_shape *shape, const float *util, const float *gate, int mode, int k,
+                float tau, int k_cap, int32_t *idx, int32_t *count, void *stream);
+
+/* Eq. 1 over the union of kept summaries and the raw window (section 3.3,
+ * n' = W + M).  For every sequence and each of its Tq queries the attended
+ * rows are Kbar[idx[0..count)] / Vbar[...] followed by the raw tokens
+ * win0 .. T-1 of K / V; O = softmax(q . keys^T / sqrt(d)) . values with fp32
+ * scores, softmax and accumulation, rounded once to the storage dtype.  The
+ * Tq queries see the whole cache and not each other (causal must be 0).
+ * count == 0 (e.g. T <= W) is valid: the raw tokens alone are attended; no
+ * rows at all gives O = 0.
+ *   Q, O  [L,B,H,Tq,d]    idx [L,B,H,k_cap]   count [L,B,H], 0 <= count <= k_cap,
+ *   every idx entry below count in [0, N_cand) (not checked: device data).
+ * Workspace: split partials, see kvev_workspace_bytes. */
+int kvev_gated_attention(const kvev_shape *shape, const void *Q, int Tq, const void *K,
+                         const void *V, const void *Kbar, const void *Vbar, const int32_t *idx,
+                         const int32_t *count, int k_cap, int causal, void *O, void *ws,
+                         size_t ws_bytes, void *stream);
+
+/* Eq. 1 over the whole cache, tokens 0 .. T-1: the baseline whose O(n) cost
+ * per new token the method removes (section 2, "Transformer Attention").
+ * Same layouts, arithmetic and workspace rule as kvev_gated_attention. */
+int kvev_dense_attention(const kvev_shape *shape, const void *Q, int Tq, const void *K,
+                         const void *V, int causal, void *O, void *ws, size_t ws_bytes,
+                         void *stream);
+
+/* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape.  `n` is Tq
+ * for the attention ops and chunk_end - chunk_begin for pool / gate; k_cap is
+ * used by KVEV_OP_GATED_ATTENTION only.  Returns 0 when none is needed or the
+ * arguments are invalid. */
+size_t kvev_workspace_bytes(int op, const kvev_shape *shape, int n, int k_cap);
+
+/* Static description of a status code. */
+const char *kvev_status_string(int status);
+
+/* Last HIP error text seen by this thread's most recent KVEV_ERR_HIP return. */
+const char *kvev_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int kvev_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVEV_H */

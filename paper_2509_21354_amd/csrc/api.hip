@@ -1,0 +1,263 @@
+// C-ABI layer: argument validation (host only, before any HIP call), launch
+// planning (split counts, workspace carving) and dispatch to the kernels.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace kvev {
+
+static thread_local char g_hip_err[256] = "";
+
+static int hip_fail(hipError_t e)
+{
+    snprintf(g_hip_err, sizeof g_hip_err, "%s", hipGetErrorString(e));
+    return KVEV_ERR_HIP;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// 0 when the shape itself is usable, else a status.
+static int check_shape(const kvev_shape *sh)
+{
+    if (!sh) return KVEV_ERR_INVALID_ARG;
+    if (sh->L < 1 || sh->B < 1 || sh->H < 1 || sh->d < 1 || sh->C < 1 || sh->T < 0 || sh->T_cap < 1 ||
+        sh->N_cap < 0 || sh->W < 0 || sh->d_sum < 1 || sh->d_g < 1)
+        return KVEV_ERR_INVALID_ARG;
+    if (sh->T > sh->T_cap || sh->T / sh->C > sh->N_cap) return KVEV_ERR_INVALID_ARG;
+    if ((int64_t)sh->L * sh->B * sh->H > (int64_t)1 << 24) return KVEV_ERR_INVALID_ARG;
+    if (sh->dtype != KVEV_F32 && sh->dtype != KVEV_BF16) return KVEV_ERR_UNSUPPORTED;
+    if (sh->d != 64 && sh->d != 128) return KVEV_ERR_UNSUPPORTED;
+    return KVEV_OK;
+}
+
+static int n_cand_of(const kvev_shape *sh) { return (sh->T > sh->W ? sh->T - sh->W : 0) / sh->C; }
+
+// ---- attention planning ---------------------------------------------------
+// Rows are split across workgroups until the launch has a few workgroups per
+// compute unit; a split never gets fewer than 64 rows (one unrolled batch of
+// the 16 lane groups).
+struct AttnPlan { int nsplit, rows_per_split; size_t ws_bytes; };
+
+static int g_attn_target_blocks = 2048;
+static int g_attn_min_rows = 64;
+
+static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
+{
+    AttnPlan p;
+    const int64_t sq = (int64_t)sh->L * sh->B * sh->H * (Tq > 0 ? Tq : 1);
+    int64_t want = (g_attn_target_blocks + sq - 1) / sq;
+    int64_t most = (n_rows + g_attn_min_rows - 1) / g_attn_min_rows;
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    int rps = (int)((n_rows + want - 1) / want);
+    rps = (rps + 15) / 16 * 16;
+    if (rps < 16) rps = 16;
+    p.rows_per_split = rps;
+    p.nsplit = n_rows > 0 ? (n_rows + rps - 1) / rps : 1;
+    p.ws_bytes = p.nsplit > 1 ? (size_t)sq * p.nsplit * (sh->d + 2) * sizeof(float) : 0;
+    return p;
+}
+
+static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
+                            const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
+                            int k_cap, int gated, int causal, void *O, void *ws, size_t ws_bytes,
+                            void *stream)
+{
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    if (!Q || !K || !V || !O || Tq < 0 || !aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
+        return KVEV_ERR_INVALID_ARG;
+    if (gated && (!Kbar || !Vbar || !idx || !count || k_cap < 0 || !aligned16(Kbar) || !aligned16(Vbar)))
+        return KVEV_ERR_INVALID_ARG;
+    if (gated && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
+    if (causal != 0) return KVEV_ERR_UNSUPPORTED;
+    if (Tq == 0) return KVEV_OK;
+    if ((int64_t)sh->L * sh->B * sh->H * Tq > (int64_t)1 << 26) return KVEV_ERR_INVALID_ARG;
+
+    const int ncand = n_cand_of(sh);
+    const int win0 = gated ? ncand * sh->C : 0;
+    const int kmax = gated ? (k_cap < ncand ? k_cap : ncand) : 0;
+    const int n_rows = kmax + sh->T - win0;
+    const AttnPlan p = plan_attn(sh, Tq, n_rows);
+    if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes || !aligned16(ws))) return KVEV_ERR_WORKSPACE;
+
+    AttnArgs a;
+    a.Q = Q; a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar; a.idx = idx; a.count = count; a.O = O;
+    a.part = p.nsplit > 1 ? static_cast<float *>(ws) : nullptr;
+    a.S = sh->L * sh->B * sh->H; a.Tq = Tq; a.d = sh->d;
+    a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = sh->N_cap; a.k_cap = k_cap;
+    a.win0 = win0; a.gated = gated;
+    a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
+    a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
+    hipError_t e = launch_attn_decode(a, sh->dtype, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+// ---- LSTM planning --------------------------------------------------------
+static bool lstm_takes_mfma(const kvev_shape *sh) { (void)sh; return false; }
+
+static size_t lstm_ws_per_step(const kvev_shape *sh)
+{
+    return lstm_takes_mfma(sh) ? (size_t)sh->L * sh->B * sh->H * 4 * sh->d_g * sizeof(float) : 0;
+}
+
+}  // namespace kvev
+
+using namespace kvev;
+
+extern "C" {
+
+int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool_mode, const kvev_mlp_w *wK,
+                    const kvev_mlp_w *wV, int chunk_begin, int chunk_end, void *Kbar, void *Vbar, void *ws,
+                    size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    if (pool_mode != KVEV_POOL_MEAN && pool_mode != KVEV_POOL_MLP) return KVEV_ERR_UNSUPPORTED;
+    if (!K || !V || !Kbar || !Vbar || !aligned16(K) || !aligned16(V) || !aligned16(Kbar) || !aligned16(Vbar))
+        return KVEV_ERR_INVALID_ARG;
+    if (chunk_begin < 0 || chunk_begin > chunk_end || chunk_end > sh->T / sh->C) return KVEV_ERR_INVALID_ARG;
+    if (pool_mode == KVEV_POOL_MLP) {
+        if (!wK || !wV) return KVEV_ERR_INVALID_ARG;
+        const void *ptrs[8] = {wK->W1, wK->b1, wK->W2, wK->b2, wV->W1, wV->b1, wV->W2, wV->b2};
+        for (const void *p : ptrs)
+            if (!p || !aligned16(p)) return KVEV_ERR_INVALID_ARG;
+        if (sizeof(float) * (16 * 2 * (size_t)sh->d + 2 * sh->d + 2 * (size_t)sh->d_sum) > 64 * 1024)
+            return KVEV_ERR_UNSUPPORTED;
+    }
+    if (chunk_begin == chunk_end) return KVEV_OK;
+    if ((int64_t)sh->L * sh->B * sh->H * (chunk_end - chunk_begin) > (int64_t)1 << 30) return KVEV_ERR_INVALID_ARG;
+
+    PoolArgs a;
+    memset(&a, 0, sizeof a);
+    a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar;
+    if (pool_mode == KVEV_POOL_MLP) {
+        a.W1K = wK->W1; a.b1K = wK->b1; a.W2K = wK->W2; a.b2K = wK->b2;
+        a.W1V = wV->W1; a.b1V = wV->b1; a.W2V = wV->W2; a.b2V = wV->b2;
+    }
+    a.L = sh->L; a.BH = sh->B * sh->H; a.d = sh->d; a.T_cap = sh->T_cap; a.C = sh->C; a.N_cap = sh->N_cap;
+    a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
+    hipError_t e = launch_pool_generic(a, sh->dtype, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, const kvev_lstm_w *w,
+                   int chunk_begin, int chunk_end, float *h, float *c, float *util, float *gate, void *ws,
+                   size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    if (!Kbar || !Vbar || !w || !h || !c || !util || !gate || !aligned16(Kbar) || !aligned16(Vbar))
+        return KVEV_ERR_INVALID_ARG;
+    const void *ptrs[6] = {w->W_ih, w->W_hh, w->b_ih, w->b_hh, w->w_s, w->b_s};
+    for (int i = 0; i < 6; ++i)
+        if (!ptrs[i] || (i < 5 && !aligned16(ptrs[i]))) return KVEV_ERR_INVALID_ARG;
+    if (chunk_begin < 0 || chunk_begin > chunk_end || chunk_end > sh->N_cap) return KVEV_ERR_INVALID_ARG;
+    if (sizeof(float) * (2 * (size_t)sh->d + 6 * (size_t)sh->d_g) > 64 * 1024 && !lstm_takes_mfma(sh))
+        return KVEV_ERR_UNSUPPORTED;
+    if (chunk_begin == chunk_end) return KVEV_OK;
+
+    LstmArgs a;
+    memset(&a, 0, sizeof a);
+    a.Kbar = Kbar; a.Vbar = Vbar;
+    a.W_ih = w->W_ih; a.W_hh = w->W_hh; a.b_ih = w->b_ih; a.b_hh = w->b_hh; a.w_s = w->w_s; a.b_s = w->b_s;
+    a.h = h; a.c = c; a.util = util; a.gate = gate;
+    a.L = sh->L; a.BH = sh->B * sh->H; a.d = sh->d; a.N_cap = sh->N_cap; a.d_g = sh->d_g;
+    a.c0 = chunk_begin; a.c1 = chunk_end;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (lstm_takes_mfma(sh)) {
+        const size_t per = lstm_ws_per_step(sh);
+        if (!ws || !aligned16(ws) || ws_bytes < per) return KVEV_ERR_WORKSPACE;
+        size_t tb = ws_bytes / per;
+        if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
+        a.tb = (int)tb;
+        a.xproj = static_cast<float *>(ws);
+        e = launch_lstm_mfma(a, st);
+    } else {
+        e = launch_lstm_generic(a, sh->dtype, st);
+    }
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_select(const kvev_shape *sh, const float *util, const float *gate, int mode, int k, float tau,
+                int k_cap, int32_t *idx, int32_t *count, void *stream)
+{
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    if (mode != KVEV_SELECT_TOPK && mode != KVEV_SELECT_THRESHOLD) return KVEV_ERR_UNSUPPORTED;
+    if (!idx || !count || k_cap < 0) return KVEV_ERR_INVALID_ARG;
+    const int ncand = n_cand_of(sh);
+    if (ncand > sh->N_cap) return KVEV_ERR_INVALID_ARG;
+    if (ncand > 16384) return KVEV_ERR_UNSUPPORTED;
+    if (mode == KVEV_SELECT_TOPK) {
+        if (!util || k < 0 || k_cap < (k < ncand ? k : ncand)) return KVEV_ERR_INVALID_ARG;
+    } else {
+        if (!gate || k_cap < ncand || tau != tau) return KVEV_ERR_INVALID_ARG;
+    }
+    SelectArgs a;
+    a.util = util; a.gate = gate; a.idx = idx; a.count = count;
+    a.S = sh->L * sh->B * sh->H; a.N_cap = sh->N_cap; a.n_cand = ncand; a.k = k; a.k_cap = k_cap;
+    a.mode = mode; a.tau = tau;
+    hipError_t e = launch_select(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_gated_attention(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
+                         const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
+                         int k_cap, int causal, void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    return attention_common(sh, Q, Tq, K, V, Kbar, Vbar, idx, count, k_cap, 1, causal, O, ws, ws_bytes, stream);
+}
+
+int kvev_dense_attention(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V, int causal,
+                         void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    return attention_common(sh, Q, Tq, K, V, nullptr, nullptr, nullptr, nullptr, 0, 0, causal, O, ws, ws_bytes,
+                            stream);
+}
+
+size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
+{
+    if (check_shape(sh) != KVEV_OK || n < 0) return 0;
+    switch (op) {
+    case KVEV_OP_LSTM_GATE: {
+        const size_t per = lstm_ws_per_step(sh);
+        const int tb = n < 64 ? n : 64;
+        return per * (size_t)tb;
+    }
+    case KVEV_OP_GATED_ATTENTION: {
+        if (k_cap < 0) return 0;
+        const int ncand = n_cand_of(sh);
+        const int kmax = k_cap < ncand ? k_cap : ncand;
+        return plan_attn(sh, n, kmax + sh->T - ncand * sh->C).ws_bytes;
+    }
+    case KVEV_OP_DENSE_ATTENTION:
+        return plan_attn(sh, n, sh->T).ws_bytes;
+    default:
+        return 0;
+    }
+}
+
+const char *kvev_status_string(int status)
+{
+    switch (status) {
+    case KVEV_OK: return "ok";
+    case KVEV_ERR_INVALID_ARG: return "invalid argument";
+    case KVEV_ERR_UNSUPPORTED: return "unsupported shape, dtype or mode";
+    case KVEV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KVEV_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *kvev_last_hip_error(void) { return g_hip_err; }
+
+int kvev_version(void) { return 100; }
+
+}  // extern "C"

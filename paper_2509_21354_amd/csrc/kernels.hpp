@@ -1,0 +1,57 @@
+// Host-visible launch interface between the C-ABI layer (api.hip) and the
+// kernel files.  Everything here is plain data; shapes were validated by the
+// caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvev {
+
+struct AttnArgs {
+    const void *Q, *K, *V, *Kbar, *Vbar;
+    const int32_t *idx, *count;
+    void *O;
+    float *part;          // split partials [S*Tq][nsplit][d+2] (o, m, l), or null when nsplit == 1
+    int S, Tq, d;
+    int T, T_cap, N_cap, k_cap;
+    int win0;             // first raw token attended (0 for the dense baseline)
+    int gated;            // 1: kept summaries precede the raw rows
+    int nsplit, rows_per_split;
+    float scale_log2e;    // log2(e) / sqrt(d)
+};
+
+struct PoolArgs {
+    const void *K, *V;
+    void *Kbar, *Vbar;
+    const void *W1K, *b1K, *W2K, *b2K, *W1V, *b1V, *W2V, *b2V;   // per layer
+    int L, BH, d, T_cap, C, N_cap, d_sum;
+    int c0, c1;
+    int mode;
+};
+
+struct LstmArgs {
+    const void *Kbar, *Vbar;
+    const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s;           // per layer
+    float *h, *c, *util, *gate;
+    float *xproj;         // workspace: [S][tb][4*d_g] fp32 input projections of a block of steps
+    int L, BH, d, N_cap, d_g;
+    int c0, c1;
+    int tb;               // steps per workspace block
+};
+
+struct SelectArgs {
+    const float *util, *gate;
+    int32_t *idx, *count;
+    int S, N_cap, n_cand, k, k_cap, mode;
+    float tau;
+};
+
+hipError_t launch_attn_decode(const AttnArgs &a, int dtype, hipStream_t st);
+hipError_t launch_attn_mq(const AttnArgs &a, hipStream_t st);           // bf16 MFMA, many queries
+hipError_t launch_select(const SelectArgs &a, hipStream_t st);
+hipError_t launch_pool_generic(const PoolArgs &a, int dtype, hipStream_t st);
+hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st);          // bf16
+hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
+hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
+
+}  // namespace kvev

@@ -1,0 +1,110 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_21354_amd import binding as kb
+from paper_2509_21354_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "kvev.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvev_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(kb.EXPORTS) == set(names)
+    L = kb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert L.kvev_version() >= 100
+    assert L.kvev_status_string(0) == b"ok"
+    assert b"workspace" in L.kvev_status_string(kb.ERR_WORKSPACE)
+
+
+FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
+
+
+def _shape(**kw):
+    return kb.make_shape(synth.CONFIGS[2], **kw)
+
+
+def test_shape_validation():
+    L = kb.lib()
+    for bad in (dict(L=0), dict(d=-1), dict(C=0), dict(T=5000), dict(N_cap=3), dict(W=-1), dict(d_g=0)):
+        sh = _shape(**bad)
+        assert L.kvev_dense_attention(ctypes.byref(sh), FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    for bad in (dict(d=96), dict(dtype=7)):
+        sh = _shape(**bad)
+        assert L.kvev_dense_attention(ctypes.byref(sh), FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_UNSUPPORTED
+    assert L.kvev_dense_attention(None, FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+
+
+def test_pointer_range_and_mode_validation():
+    L = kb.lib()
+    sh = _shape()
+    r = ctypes.byref(sh)
+    odd = ctypes.c_void_p(0x1004)
+    w = kb.MlpW(0x1000, 0x1000, 0x1000, 0x1000)
+    wr = ctypes.byref(w)
+    # attention
+    assert L.kvev_dense_attention(r, None, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_dense_attention(r, odd, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_dense_attention(r, FAKE, -1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 1, FAKE, None, 0, None) == kb.ERR_UNSUPPORTED
+    assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_WORKSPACE
+    assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, 64, None) == kb.ERR_WORKSPACE
+    assert L.kvev_dense_attention(r, FAKE, 0, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.OK   # Tq = 0: nothing to do
+    assert L.kvev_gated_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, None, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_gated_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    # pool
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, 5, wr, wr, 0, 1, FAKE, FAKE, None, 0, None) == kb.ERR_UNSUPPORTED
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, None, wr, 0, 1, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, wr, wr, 3, 2, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, wr, wr, 0, 129, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, wr, wr, -1, 4, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MEAN, None, None, 7, 7, FAKE, FAKE, None, 0, None) == kb.OK  # empty range
+    # a trailing partial chunk is not poolable
+    sh2 = _shape(T=4095)
+    assert L.kvev_chunk_pool(ctypes.byref(sh2), FAKE, FAKE, kb.POOL_MEAN, None, None, 0, 128, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    # gate
+    lw = kb.LstmW(*([0x1000] * 6))
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, None, 0, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 0, 129, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 2, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 4, 4, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.OK
+    lw0 = kb.LstmW(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw0), 0, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    # select
+    assert L.kvev_select(r, FAKE, None, 9, 4, 0.0, 4, FAKE, FAKE, None) == kb.ERR_UNSUPPORTED
+    assert L.kvev_select(r, None, None, kb.SELECT_TOPK, 4, 0.0, 4, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_select(r, FAKE, None, kb.SELECT_TOPK, -1, 0.0, 4, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_select(r, FAKE, None, kb.SELECT_TOPK, 32, 0.0, 31, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_select(r, None, FAKE, kb.SELECT_THRESHOLD, 0, 0.5, 119, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_select(r, None, FAKE, kb.SELECT_THRESHOLD, 0, float("nan"), 120, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+
+
+def test_workspace_query():
+    sh = _shape()
+    dense = kb.workspace_bytes(kb.OP_DENSE_ATTENTION, sh, 1)
+    gated = kb.workspace_bytes(kb.OP_GATED_ATTENTION, sh, 1, 32)
+    assert dense > 0 and gated >= 0 and dense % 8 == 0
+    assert kb.workspace_bytes(kb.OP_SELECT, sh, 1) == 0
+    assert kb.workspace_bytes(kb.OP_CHUNK_POOL, sh, 128) == 0
+    assert kb.workspace_bytes(kb.OP_DENSE_ATTENTION, _shape(L=0), 1) == 0
+    big = kb.make_shape(synth.CONFIGS[3])
+    assert kb.workspace_bytes(kb.OP_GATED_ATTENTION, big, 1, 64) == 0    # 8192 sequences: no split needed
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(kb, "_lib", None)
+    monkeypatch.setattr(kb, "LIB_PATH", str(tmp_path / "libkvev.so"))
+    with pytest.raises(FileNotFoundError):
+        kb.lib()
