@@ -98,11 +98,25 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
 }
 
 // ---- LSTM planning --------------------------------------------------------
-static bool lstm_takes_mfma(const kvev_shape *sh) { (void)sh; return false; }
+// The matrix-core gate takes bf16 storage with d_g a multiple of 64 up to 512;
+// its scratch holds, per step of a block, one fp32 pre-activation per gate row
+// for every 16-sequence group (groups are padded and never straddle layers).
+static bool lstm_takes_mfma(const kvev_shape *sh)
+{
+    return sh->dtype == KVEV_BF16 && (sh->d_g == 64 || sh->d_g == 128 || sh->d_g == 256 || sh->d_g == 512);
+}
+
+// W_hh re-laid in MFMA fragment order sits at the front of the scratch.
+static size_t lstm_ws_pack(const kvev_shape *sh)
+{
+    return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * sh->d_g * 2 : 0;
+}
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
 {
-    return lstm_takes_mfma(sh) ? (size_t)sh->L * sh->B * sh->H * 4 * sh->d_g * sizeof(float) : 0;
+    if (!lstm_takes_mfma(sh)) return 0;
+    const size_t groups = (size_t)sh->L * ((sh->B * sh->H + 15) / 16);
+    return groups * 16 * 4 * sh->d_g * sizeof(float);
 }
 
 }  // namespace kvev
@@ -172,12 +186,13 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (lstm_takes_mfma(sh)) {
-        const size_t per = lstm_ws_per_step(sh);
-        if (!ws || !aligned16(ws) || ws_bytes < per) return KVEV_ERR_WORKSPACE;
-        size_t tb = ws_bytes / per;
+        const size_t per = lstm_ws_per_step(sh), pack = lstm_ws_pack(sh);
+        if (!ws || !aligned16(ws) || ws_bytes < pack + per) return KVEV_ERR_WORKSPACE;
+        size_t tb = (ws_bytes - pack) / per;
         if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
         a.tb = (int)tb;
-        a.xproj = static_cast<float *>(ws);
+        a.whh_packed = static_cast<const bf16x8_t *>(ws);
+        a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
     } else {
         e = launch_lstm_generic(a, sh->dtype, st);
@@ -228,8 +243,8 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
     switch (op) {
     case KVEV_OP_LSTM_GATE: {
         const size_t per = lstm_ws_per_step(sh);
-        const int tb = n < 64 ? n : 64;
-        return per * (size_t)tb;
+        const int tb = n < 128 ? n : 128;
+        return per == 0 ? 0 : lstm_ws_pack(sh) + per * (size_t)(tb < 1 ? 1 : tb);
     }
     case KVEV_OP_GATED_ATTENTION: {
         if (k_cap < 0) return 0;

@@ -33,7 +33,8 @@ struct LstmArgs {
     const void *Kbar, *Vbar;
     const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s;           // per layer
     float *h, *c, *util, *gate;
-    float *xproj;         // workspace: [S][tb][4*d_g] fp32 input projections of a block of steps
+    float *xproj;         // workspace: fp32 input projections of a block of steps (fragment layout)
+    const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *whh_packed;   // workspace: W_hh in fragment order
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block

@@ -1,5 +1,334 @@
+// Recurrent gate, Eq. 3 of the paper, bf16 storage, on the matrix cores.
+//
+// Two kernels per block of steps:
+//   lstm_inproj_kernel  the time-parallel half  W_ih [Kbar_t ; Vbar_t] + b_ih + b_hh
+//                       for every step of the block (bf16 x bf16 products are
+//                       exact in the fp32 accumulator), written to scratch in
+//                       the exact register layout the recurrence reads back;
+//   lstm_rec_kernel     the sequential half: one workgroup owns 16 sequences
+//                       of one layer and walks them through the block's steps.
+//
+// Tiling (both kernels): v_mfma_f32_16x16x32_bf16 with the gate rows as the M
+// side (A operand = weight rows, read straight from global memory / L2 in
+// 16-byte pieces) and the 16 sequences as the N side (B operand = h or x).
+// A wave owns UT tiles of 16 hidden units for all four gates, so i, f, g, o of a
+// unit meet in the same lane and the cell update needs no data movement; with
+// UT = 2 a workgroup has two waves per SIMD and one wave's weight loads hide
+// behind the other's MFMAs.  Within a wave the unit tiles are walked one after the
+// other (4 live accumulators), which leaves the registers to a deep ring of
+// prefetched weight fragments.
+//
+// The state h is fp32.  To feed it to the bf16 matrix cores without losing it,
+// h is cut into three bf16 terms (h = hi + mid + lo, exact to 24 bits) and the
+// product is taken once per term; every partial product is exact and the sum
+// is accumulated in fp32, so the result has fp32 accuracy.
 #include "common.hpp"
 #include "kernels.hpp"
+
 namespace kvev {
-hipError_t launch_lstm_mfma(const LstmArgs &, hipStream_t) { return hipErrorNotSupported; }
+
+// Gate nonlinearities through the hardware exp2 and reciprocal (about 1 ulp
+// each).  Their absolute error stays below ~2e-7 everywhere, which is what the
+// cell update needs (it consumes the values, not their logarithms): the
+// relative error of exp(x) grows like |x| * 2^-24, but it is multiplied by
+// s(1-s), which decays exponentially.
+__device__ __forceinline__ float sigmoid_hw(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f));
 }
+__device__ __forceinline__ float tanh_hw(float x)
+{
+    return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
+}
+
+constexpr int kTT = 4;   // steps per wave pass of the input projection
+
+// Geometry shared by the three kernels: unit tiles per wave, waves per workgroup.
+template <int DG> struct Geo {
+    static constexpr int UT = DG == 512 ? 4 : 2;   // keeps the workgroup at 8 waves (256 registers per lane)
+    static constexpr int NW = DG / (16 * UT);
+    static constexpr int KS = DG / 32;
+    static constexpr int THREADS = NW * 64;
+};
+
+// Scratch layout: 1 KiB blocks of 64 lanes x 4 floats, one per
+// (sequence group, step of the block, wave, unit tile, gate).
+template <int DG>
+__device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, int ut, int q)
+{
+    return ((((size_t)group * tb + tt) * Geo<DG>::NW + wave) * Geo<DG>::UT + ut) * 4 + q;
+}
+
+template <int DG, int D>
+__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb)
+{
+    constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, g4 = lane >> 4;
+    const int gpl = (a.BH + 15) / 16;
+    const int l = blockIdx.x / gpl, grp = blockIdx.x % gpl;
+    const int sl = min(grp * 16 + n, a.BH - 1);
+    const size_t s = (size_t)l * a.BH + sl;
+    const int tt0 = blockIdx.y * kTT;
+
+    const bf16_t *Kbar = static_cast<const bf16_t *>(a.Kbar), *Vbar = static_cast<const bf16_t *>(a.Vbar);
+    bf16x8_t xb[kTT][KS];
+#pragma unroll
+    for (int j = 0; j < kTT; ++j) {
+        const int t = t0 + min(tt0 + j, nb - 1);
+        const size_t row = (s * a.N_cap + t) * D;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int e = ks * 32 + g4 * 8;
+            const bf16_t *src = e < D ? Kbar + row + e : Vbar + row + (e - D);
+            xb[j][ks] = *reinterpret_cast<const bf16x8_t *>(src);
+        }
+    }
+    const bf16_t *W = static_cast<const bf16_t *>(a.W_ih) + (size_t)l * 4 * DG * 2 * D;
+    const bf16_t *b_ih = static_cast<const bf16_t *>(a.b_ih) + (size_t)l * 4 * DG;
+    const bf16_t *b_hh = static_cast<const bf16_t *>(a.b_hh) + (size_t)l * 4 * DG;
+    for (int ut = 0; ut < UT; ++ut) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row0 = q * DG + wave * 16 * UT + ut * 16;
+            bf16x8_t wf[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                wf[ks] = *reinterpret_cast<const bf16x8_t *>(W + (size_t)(row0 + n) * 2 * D + ks * 32 + g4 * 8);
+            float bias[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                bias[r] = bf16_to_f32(b_ih[row0 + 4 * g4 + r]) + bf16_to_f32(b_hh[row0 + 4 * g4 + r]);
+#pragma unroll
+            for (int j = 0; j < kTT; ++j) {
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], xb[j][ks], acc, 0, 0, 0);
+                if (tt0 + j < nb) {
+                    float4 o = make_float4(acc[0] + bias[0], acc[1] + bias[1], acc[2] + bias[2], acc[3] + bias[3]);
+                    float *dst = a.xproj + xp_block<DG>(blockIdx.x, a.tb, tt0 + j, wave, ut, q) * 256 + lane * 4;
+                    *reinterpret_cast<float4 *>(dst) = o;
+                }
+            }
+        }
+    }
+}
+
+// W_hh re-laid in A-fragment order so that every wave-level load of the
+// recurrence is one contiguous 1 KiB piece (the row-major matrix would give 16
+// half-used cache lines per load): [layer][wave][unit tile][k-step][gate][lane][8].
+template <int DG>
+__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, bf16x8_t *packed, int L)
+{
+    constexpr int NW = Geo<DG>::NW, KS = Geo<DG>::KS, UT = Geo<DG>::UT;
+    const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;         // one 16-byte fragment per thread
+    const size_t total = (size_t)L * NW * KS * UT * 4 * 64;
+    if (frag >= total) return;
+    const int lane = frag % 64;
+    size_t r = frag / 64;
+    const int q = r % 4; r /= 4;
+    const int ks = r % KS; r /= KS;
+    const int ut = r % UT; r /= UT;
+    const int wave = r % NW;
+    const int l = (int)(r / NW);
+    const int n = lane & 15, g4 = lane >> 4;
+    const bf16_t *src = W_hh + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * DG + ks * 32 + g4 * 8;
+    packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
+}
+
+template <int DG>
+__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, int t0, int nb)
+{
+    constexpr int NW = Geo<DG>::NW, KS = Geo<DG>::KS, UT = Geo<DG>::UT, HP = DG + 8;
+    // The weight fragments of a wave form one stream of ITEMS = UT*KS items (4
+    // fragments each: gates i,f,g,o of one unit tile at one k-step), read from L2
+    // through a ring of NSLOT register buffers that runs NSLOT-1 items ahead of the
+    // MFMAs and wraps into the next time step, so the cell update and the barrier
+    // overlap with loads already in flight.
+    constexpr int ITEMS = UT * KS;
+    constexpr int NSLOT = (Geo<DG>::THREADS >= 1024 || ITEMS < 8) ? 4 : 8;
+    constexpr int PF = NSLOT - 1;
+    static_assert(ITEMS % NSLOT == 0, "slot rotation must line up with the item loop");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t *s_h = reinterpret_cast<bf16_t *>(smem_raw);                                   // [2][3][16][HP]
+    float *s_up = reinterpret_cast<float *>(smem_raw + (size_t)2 * 3 * 16 * HP * sizeof(bf16_t));   // [2][NW][16]
+
+    // wave index as a scalar, so that per-wave base addresses live in SGPRs and every
+    // fragment load is (scalar base) + (one lane-offset VGPR) + (immediate)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g4 = lane >> 4;
+    const int gpl = (a.BH + 15) / 16;
+    const int l = blockIdx.x / gpl, grp = blockIdx.x % gpl;
+    const bool live = grp * 16 + n < a.BH;
+    const size_t s = (size_t)l * a.BH + min(grp * 16 + n, a.BH - 1);
+
+    const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
+    const float b_s = bf16_to_f32(static_cast<const bf16_t *>(a.b_s)[l]);
+
+    // state of (sequence n, units 16*UT*wave + 16*ut + 4*g4 + r) lives in this lane
+    float c_reg[UT][4], h_reg[UT][4], ws_reg[UT][4];
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int unit = wave * 16 * UT + ut * 16 + 4 * g4 + r;
+            c_reg[ut][r] = live ? a.c[s * DG + unit] : 0.f;
+            h_reg[ut][r] = live ? a.h[s * DG + unit] : 0.f;
+            ws_reg[ut][r] = bf16_to_f32(w_s[unit]);
+        }
+
+    // this wave's packed A fragments: fragment (item, q) of this lane sits at wp[(item*4 + q)*64]
+    const unsigned char *wbase = reinterpret_cast<const unsigned char *>(a.whh_packed + ((size_t)l * NW + wave) * KS * UT * 4 * 64);
+    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
+        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(blockIdx.x, a.tb, 0, wave, 0, 0) * 64);
+    const uint32_t lane16 = lane * 16;
+    bf16_t *h_wr = s_h + (size_t)n * HP + wave * 16 * UT + 4 * g4;          // + (buf*3+p)*16*HP + ut*16
+    const bf16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;                // + (buf*3+p)*16*HP + ks*32
+
+    auto publish_h = [&](int buf, int ut) {
+        {
+            float hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int r = 0; r < 4; r += 2) {
+                const uint32_t ph = pack_bf16x2(h_reg[ut][r], h_reg[ut][r + 1]);
+                hi[r] = __uint_as_float(ph << 16); hi[r + 1] = __uint_as_float(ph & 0xFFFF0000u);
+                const float r0 = h_reg[ut][r] - hi[r], r1 = h_reg[ut][r + 1] - hi[r + 1];
+                const uint32_t pm = pack_bf16x2(r0, r1);
+                mid[r] = __uint_as_float(pm << 16); mid[r + 1] = __uint_as_float(pm & 0xFFFF0000u);
+                lo[r] = r0 - mid[r]; lo[r + 1] = r1 - mid[r + 1];
+            }
+            uint2 v;
+            v.x = pack_bf16x2(hi[0], hi[1]); v.y = pack_bf16x2(hi[2], hi[3]);
+            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 0) * 16 * HP + ut * 16) = v;
+            v.x = pack_bf16x2(mid[0], mid[1]); v.y = pack_bf16x2(mid[2], mid[3]);
+            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 1) * 16 * HP + ut * 16) = v;
+            v.x = pack_bf16x2(lo[0], lo[1]); v.y = pack_bf16x2(lo[2], lo[3]);
+            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 2) * 16 * HP + ut * 16) = v;
+        }
+    };
+
+    bf16x8_t wbuf[NSLOT][4];
+    auto load_w = [&](int slot, int item) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wbuf[slot][q] = *reinterpret_cast<const bf16x8_t *>(wbase + (size_t)item * 4096 + (lane16 + q * 1024));
+    };
+#pragma unroll
+    for (int i = 0; i < PF; ++i) load_w(i, i);
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) publish_h(0, ut);
+    __syncthreads();
+
+    for (int tt = 0; tt < nb; ++tt) {
+        const int cur = tt & 1, nxt = cur ^ 1;
+        float upart = 0.f;
+#pragma unroll
+        for (int ut = 0; ut < UT; ++ut) {
+            // the accumulators start from the step's input projection (read back in the
+            // C-fragment layout it was written in), so the MFMA chain adds W_hh h on top
+            f32x4_t acc[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                acc[q] = *reinterpret_cast<const f32x4_t *>(xbase + ((size_t)tt * NW * UT + ut) * 4096 + (lane16 + q * 1024));
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int item = ut * KS + ks;
+                load_w((item + PF) % NSLOT, (item + PF) % ITEMS);
+                bf16x8_t hb[3];
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+                    hb[p] = *reinterpret_cast<const bf16x8_t *>(h_rd + (size_t)(cur * 3 + p) * 16 * HP + ks * 32);
+#pragma unroll
+                for (int p = 2; p >= 0; --p)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wbuf[item % NSLOT][q], hb[p], acc[q], 0, 0, 0);
+                // the prefetch depth is the ring, not whatever the scheduler can hoist
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float ig = sigmoid_hw(acc[0][r]);
+                const float fg = sigmoid_hw(acc[1][r]);
+                const float gg = tanh_hw(acc[2][r]);
+                const float og = sigmoid_hw(acc[3][r]);
+                const float cn = fmaf(fg, c_reg[ut][r], ig * gg);
+                c_reg[ut][r] = cn;
+                float hn = og * tanh_hw(cn);
+                asm volatile("" : "+v"(hn));     // opaque to the optimiser: hn is the rounded product from here on
+                h_reg[ut][r] = hn;
+                upart = fmaf(ws_reg[ut][r], hn, upart);
+            }
+            publish_h(nxt, ut);
+        }
+        upart += __shfl_xor(upart, 16);
+        upart += __shfl_xor(upart, 32);
+        if (g4 == 0) s_up[(cur * NW + wave) * 16 + n] = upart;
+        __syncthreads();
+        if (tid < 16) {
+            float u = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) u += s_up[(cur * NW + w) * 16 + tid];
+            u += b_s;
+            if (live) {
+                a.util[s * a.N_cap + t0 + tt] = u;
+                a.gate[s * a.N_cap + t0 + tt] = sigmoid_hw(u);
+            }
+        }
+    }
+
+    if (live) {
+#pragma unroll
+        for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int unit = wave * 16 * UT + ut * 16 + 4 * g4 + r;
+                a.c[s * DG + unit] = c_reg[ut][r];
+                a.h[s * DG + unit] = h_reg[ut][r];
+            }
+    }
+}
+
+template <int DG>
+static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
+{
+    const int gpl = (a.BH + 15) / 16;
+    const unsigned groups = (unsigned)(a.L * gpl);
+    const size_t lds = (size_t)2 * 3 * 16 * (DG + 8) * sizeof(bf16_t) + (size_t)2 * Geo<DG>::NW * 16 * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_kernel<DG>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    {
+        const size_t frags = (size_t)a.L * 4 * DG * DG / 8;
+        hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const bf16_t *>(a.W_hh), const_cast<bf16x8_t *>(a.whh_packed), a.L);
+    }
+    for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
+        const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
+        const dim3 grid_in(groups, (unsigned)((nb + kTT - 1) / kTT));
+        if (a.d == 64)
+            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64>), grid_in, dim3(Geo<DG>::THREADS), 0, st, a, t0, nb);
+        else
+            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128>), grid_in, dim3(Geo<DG>::THREADS), 0, st, a, t0, nb);
+        hipLaunchKernelGGL((lstm_rec_kernel<DG>), dim3(groups), dim3(Geo<DG>::THREADS), lds, st, a, t0, nb);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st)
+{
+    switch (a.d_g) {
+    case 64: return launch_dg<64>(a, st);
+    case 128: return launch_dg<128>(a, st);
+    case 256: return launch_dg<256>(a, st);
+    case 512: return launch_dg<512>(a, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace kvev
