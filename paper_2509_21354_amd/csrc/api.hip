@@ -156,7 +156,10 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     }
     a.L = sh->L; a.BH = sh->B * sh->H; a.d = sh->d; a.T_cap = sh->T_cap; a.C = sh->C; a.N_cap = sh->N_cap;
     a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
-    hipError_t e = launch_pool_generic(a, sh->dtype, static_cast<hipStream_t>(stream));
+    // bf16 storage with a hidden width the 16x16x32 tiling divides goes to the matrix cores
+    const bool mfma = sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
+    hipError_t e = mfma ? launch_pool_mfma(a, static_cast<hipStream_t>(stream))
+                        : launch_pool_generic(a, sh->dtype, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 

@@ -1,0 +1,204 @@
+// Chunk aggregation, Eq. 2 of the paper, bf16 storage.
+//
+// The op reads every raw key and value once (2*C*d elements per chunk) and
+// writes one summary pair: about 8 flop per byte, far below the machine's
+// ridge, so the kernel is a streaming reader with the MLP as a side dish.  A
+// workgroup owns a tile of 16 (sequence, chunk) rows of one layer:
+//   1. each wave streams 4 of the rows: a 16-lane group owns a token at a time
+//      (one 16-byte load per lane, 1 KiB contiguous per wave-level load), sums
+//      in fp32, and the chunk means land in LDS as fp32;
+//   2. layer 1 and 3. layer 2 run on v_mfma_f32_16x16x32_bf16 with the weight
+//      rows as the A operand (read from global memory; the four weight
+//      matrices total 128 KiB and stay in cache) and the 16 tile rows as B.
+// The fp32 means and activations are fed to the bf16 matrix cores as three
+// bf16 terms each (x = hi + mid + lo, exact to 24 bits): weights are bf16, so
+// every partial product is exact and the fp32 accumulation gives fp32-grade
+// results, which is what keeps the stored summaries equal to a double
+// precision evaluation except for rare last-bit flips.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace kvev {
+
+struct Split3 { bf16x8_t hi, mid, lo; };
+
+// 8 fp32 -> three bf16x8 terms whose sum is the input (to 24 bits)
+__device__ __forceinline__ Split3 split3(const float (&x)[8])
+{
+    uint32_t h[4], m[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
+        const float r0 = x[2 * i] - __uint_as_float(h[i] << 16);
+        const float r1 = x[2 * i + 1] - __uint_as_float(h[i] & 0xFFFF0000u);
+        m[i] = pack_bf16x2(r0, r1);
+        const float s0 = r0 - __uint_as_float(m[i] << 16);
+        const float s1 = r1 - __uint_as_float(m[i] & 0xFFFF0000u);
+        l[i] = pack_bf16x2(s0, s1);
+    }
+    Split3 o;
+    o.hi = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+    o.mid = __builtin_bit_cast(bf16x8_t, make_uint4(m[0], m[1], m[2], m[3]));
+    o.lo = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+    return o;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
+{
+    constexpr int EPL = D / 16;          // elements per lane of a 16-lane row group
+    constexpr int XP = D + 4;            // padded fp32 row of the mean tile
+    extern __shared__ __align__(16) float smem[];
+    float *xm = smem;                    // [2][16][XP]   chunk means (K then V)
+    float *act = smem + 2 * 16 * XP;     // [2][16][d_sum + 4]
+    const int AP = a.d_sum + 4;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g4 = lane >> 4;
+    const int nch = a.c1 - a.c0;
+    const int rows_per_layer = a.BH * nch;
+    const int tiles_per_layer = (rows_per_layer + 15) / 16;
+    const int l = blockIdx.x / tiles_per_layer;
+    const int row0 = (blockIdx.x % tiles_per_layer) * 16;
+
+    const bf16_t *K = static_cast<const bf16_t *>(a.K), *V = static_cast<const bf16_t *>(a.V);
+
+    // ---- 1. stream the chunks, fp32 means to LDS ------------------------------
+    for (int i = 0; i < 4; ++i) {
+        const int rt = wave * 4 + i;                         // row within the tile
+        const int r = min(row0 + rt, rows_per_layer - 1);    // clamped: a tail row repeats the last one
+        const size_t s = (size_t)l * a.BH + r / nch;
+        const int c = a.c0 + r % nch;
+        const size_t tok0 = (s * a.T_cap + (size_t)c * a.C) * D + n * EPL;
+        float sk[EPL], sv[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sk[e] = sv[e] = 0.f;
+        for (int j0 = 0; j0 < a.C; j0 += 32) {
+            Raw<bf16_t, EPL> xk[8], xv[8];
+            bool ok[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + g4 + 4 * u;
+                ok[u] = j < a.C;
+                const size_t off = tok0 + (size_t)(ok[u] ? j : a.C - 1) * D;
+                xk[u].load(K + off);
+                xv[u].load(V + off);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (ok[u]) {
+                    float fk[EPL], fv[EPL];
+                    xk[u].get(fk);
+                    xv[u].get(fv);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) { sk[e] += fk[e]; sv[e] += fv[e]; }
+                }
+        }
+        const float cf = (float)a.C;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            sk[e] += __shfl_xor(sk[e], 16); sk[e] += __shfl_xor(sk[e], 32);
+            sv[e] += __shfl_xor(sv[e], 16); sv[e] += __shfl_xor(sv[e], 32);
+        }
+        if (g4 == 0) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                xm[(0 * 16 + rt) * XP + n * EPL + e] = sk[e] / cf;
+                xm[(1 * 16 + rt) * XP + n * EPL + e] = sv[e] / cf;
+            }
+        }
+    }
+    __syncthreads();
+
+    // this lane's tile row as an output address (C layout: column n = tile row)
+    const int r_out = row0 + n;
+    const bool live = r_out < rows_per_layer;
+    const int r_c = min(r_out, rows_per_layer - 1);
+    const size_t out_row = (((size_t)l * a.BH + r_c / nch) * a.N_cap + (a.c0 + r_c % nch)) * D;
+    bf16_t *Kb = static_cast<bf16_t *>(a.Kbar), *Vb = static_cast<bf16_t *>(a.Vbar);
+
+    if (a.mode == KVEV_POOL_MEAN) {
+        for (int i = tid; i < 2 * 16 * (D / 2); i += 256) {
+            const int kv = i / (16 * (D / 2)), rt = (i / (D / 2)) % 16, e = (i % (D / 2)) * 2;
+            const int r = row0 + rt;
+            if (r < rows_per_layer) {
+                const size_t o = (((size_t)l * a.BH + r / nch) * a.N_cap + (a.c0 + r % nch)) * D + e;
+                *reinterpret_cast<uint32_t *>((kv ? Vb : Kb) + o) =
+                    pack_bf16x2(xm[(kv * 16 + rt) * XP + e], xm[(kv * 16 + rt) * XP + e + 1]);
+            }
+        }
+        return;
+    }
+
+    // ---- 2. layer 1: act = GELU(W1 xbar + b1), tiles of 16 hidden units ------
+    const int ds = a.d_sum;
+    const int tiles1 = ds / 16;
+    for (int t = wave; t < 2 * tiles1; t += 4) {
+        const int kv = t / tiles1, u0 = (t % tiles1) * 16;
+        const bf16_t *W1 = static_cast<const bf16_t *>(kv ? a.W1V : a.W1K) + ((size_t)l * ds + u0 + n) * D + g4 * 8;
+        const bf16_t *b1 = static_cast<const bf16_t *>(kv ? a.b1V : a.b1K) + (size_t)l * ds + u0 + 4 * g4;
+        f32x4_t acc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b1[r]);
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) {
+            const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W1 + ks * 32);
+            float x[8];
+            const float *xr = xm + (kv * 16 + n) * XP + ks * 32 + g4 * 8;
+            const float4 x0 = *reinterpret_cast<const float4 *>(xr), x1 = *reinterpret_cast<const float4 *>(xr + 4);
+            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+            const Split3 sp = split3(x);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.lo, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.mid, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.hi, acc, 0, 0, 0);
+        }
+        float4 g;
+        g.x = gelu_erf(acc[0]); g.y = gelu_erf(acc[1]); g.z = gelu_erf(acc[2]); g.w = gelu_erf(acc[3]);
+        *reinterpret_cast<float4 *>(act + (kv * 16 + n) * AP + u0 + 4 * g4) = g;
+    }
+    __syncthreads();
+
+    // ---- 3. layer 2: summary = W2 act + b2, tiles of 16 output elements ------
+    constexpr int tiles2 = D / 16;
+    for (int t = wave; t < 2 * tiles2; t += 4) {
+        const int kv = t / tiles2, e0 = (t % tiles2) * 16;
+        const bf16_t *W2 = static_cast<const bf16_t *>(kv ? a.W2V : a.W2K) + ((size_t)l * D + e0 + n) * ds + g4 * 8;
+        const bf16_t *b2 = static_cast<const bf16_t *>(kv ? a.b2V : a.b2K) + (size_t)l * D + e0 + 4 * g4;
+        f32x4_t acc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b2[r]);
+        for (int ks = 0; ks < ds / 32; ++ks) {
+            const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W2 + ks * 32);
+            float x[8];
+            const float *xr = act + (kv * 16 + n) * AP + ks * 32 + g4 * 8;
+            const float4 x0 = *reinterpret_cast<const float4 *>(xr), x1 = *reinterpret_cast<const float4 *>(xr + 4);
+            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+            const Split3 sp = split3(x);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.lo, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.mid, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.hi, acc, 0, 0, 0);
+        }
+        if (live) {
+            uint2 o;
+            o.x = pack_bf16x2(acc[0], acc[1]);
+            o.y = pack_bf16x2(acc[2], acc[3]);
+            *reinterpret_cast<uint2 *>((kv ? Vb : Kb) + out_row + e0 + 4 * g4) = o;
+        }
+    }
+}
+
+hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st)
+{
+    const int nch = a.c1 - a.c0;
+    const size_t rows_per_layer = (size_t)a.BH * nch;
+    const size_t blocks = (size_t)a.L * ((rows_per_layer + 15) / 16);
+    if (blocks == 0) return hipSuccess;
+    const size_t lds = sizeof(float) * (2 * 16 * ((size_t)a.d + 4) + 2 * 16 * ((size_t)a.d_sum + 4));
+    if (a.d == 64)
+        hipLaunchKernelGGL((pool_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((pool_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace kvev
