@@ -38,12 +38,19 @@ static int n_cand_of(const kvev_shape *sh) { return (sh->T > sh->W ? sh->T - sh-
 
 // ---- attention planning ---------------------------------------------------
 // Rows are split across workgroups until the launch has a few workgroups per
-// compute unit; a split never gets fewer than 64 rows (one unrolled batch of
-// the 16 lane groups).
+// compute unit; a split never gets fewer than a few hundred rows, below which
+// the second (combine) launch costs more than the extra parallelism returns.
 struct AttnPlan { int nsplit, rows_per_split; size_t ws_bytes; };
 
-static int g_attn_target_blocks = 2048;
-static int g_attn_min_rows = 64;
+static int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
+}
+// tuning knobs (environment, read once): workgroups wanted per launch and the
+// smallest split worth a workgroup
+static const int g_attn_target_blocks = env_int("KVEV_ATTN_TARGET_BLOCKS", 1024);
+static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", 512);
 
 static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 {

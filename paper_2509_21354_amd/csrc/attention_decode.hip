@@ -144,22 +144,50 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
     }
 }
 
-// Merge of the split partials (o[D], m, l) of one (sequence, query): plain
-// log-sum-exp combination in a fixed order.
+// Merge of the split partials (o[D], m, l) of one (sequence, query): a
+// log-sum-exp combination in a fixed order (tree over lanes, then waves).  The
+// splits' maxima and sums are reduced across the workgroup first, so that the
+// D-wide accumulation only issues independent loads.
 template <typename T, int D>
 __global__ __launch_bounds__(D) void attn_combine_kernel(const float *part, int nsplit, T *O)
 {
-    const int sq = blockIdx.x, t = threadIdx.x;
+    extern __shared__ float s_w[];                 // [nsplit] weights exp2(m_i - M)
+    __shared__ float s_red[2][D / 64];
+    const int sq = blockIdx.x, t = threadIdx.x, wave = t >> 6;
     const float *p = part + (size_t)sq * nsplit * (D + 2);
-    float M = kNegBig;
-    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, p[(size_t)i * (D + 2) + D]);
-    float L = 0.f, acc = 0.f;
-    for (int i = 0; i < nsplit; ++i) {
+    float mloc = kNegBig;
+    for (int i = t; i < nsplit; i += D) mloc = fmaxf(mloc, p[(size_t)i * (D + 2) + D]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
+    if ((t & 63) == 0) s_red[0][wave] = mloc;
+    __syncthreads();
+    float M = s_red[0][0];
+#pragma unroll
+    for (int w = 1; w < D / 64; ++w) M = fmaxf(M, s_red[0][w]);
+    float lloc = 0.f;
+    for (int i = t; i < nsplit; i += D) {
         const float *pi = p + (size_t)i * (D + 2);
         const float f = exp2f(pi[D] - M);
-        L += pi[D + 1] * f;
-        acc += pi[t] * f;
+        s_w[i] = f;
+        lloc += pi[D + 1] * f;
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) lloc += __shfl_xor(lloc, off);
+    if ((t & 63) == 0) s_red[1][wave] = lloc;
+    __syncthreads();
+    float L = s_red[1][0];
+#pragma unroll
+    for (int w = 1; w < D / 64; ++w) L += s_red[1][w];
+    float acc = 0.f;
+    int i = 0;
+    for (; i + 8 <= nsplit; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(size_t)(i + u) * (D + 2) + t];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = fmaf(v[u], s_w[i + u], acc);
+    }
+    for (; i < nsplit; ++i) acc = fmaf(p[(size_t)i * (D + 2) + t], s_w[i], acc);
     Storage<T>::store(O + (size_t)sq * D + t, L > 0.f ? acc / L : 0.f);
 }
 
@@ -171,8 +199,8 @@ static hipError_t launch_decode_t(const AttnArgs &a, hipStream_t st)
     if (blocks == 0) return hipSuccess;
     hipLaunchKernelGGL((attn_decode_kernel<T, D, U>), dim3(blocks), dim3(256), 0, st, a);
     if (a.nsplit > 1)
-        hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * a.Tq)), dim3(D), 0,
-                           st, a.part, a.nsplit, static_cast<T *>(a.O));
+        hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * a.Tq)), dim3(D),
+                           (size_t)a.nsplit * sizeof(float), st, a.part, a.nsplit, static_cast<T *>(a.O));
     return hipGetLastError();
 }
 
