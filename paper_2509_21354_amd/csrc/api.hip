@@ -69,6 +69,8 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
     return p;
 }
 
+static bool attn_takes_mq(const kvev_shape *sh, int Tq) { return sh->dtype == KVEV_BF16 && Tq >= 16; }
+
 static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
                             const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
                             int k_cap, int gated, int causal, void *O, void *ws, size_t ws_bytes,
@@ -89,7 +91,9 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     const int win0 = gated ? ncand * sh->C : 0;
     const int kmax = gated ? (k_cap < ncand ? k_cap : ncand) : 0;
     const int n_rows = kmax + sh->T - win0;
-    const AttnPlan p = plan_attn(sh, Tq, n_rows);
+    // a frame of queries on bf16 storage goes to the matrix-core kernel (no split, no scratch)
+    const bool mq = attn_takes_mq(sh, Tq);
+    const AttnPlan p = mq ? AttnPlan{1, n_rows, 0} : plan_attn(sh, Tq, n_rows);
     if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes || !aligned16(ws))) return KVEV_ERR_WORKSPACE;
 
     AttnArgs a;
@@ -100,7 +104,8 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     a.win0 = win0; a.gated = gated;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
-    hipError_t e = launch_attn_decode(a, sh->dtype, static_cast<hipStream_t>(stream));
+    hipError_t e = mq ? launch_attn_mq(a, static_cast<hipStream_t>(stream))
+                      : launch_attn_decode(a, sh->dtype, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 
@@ -260,10 +265,10 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
         if (k_cap < 0) return 0;
         const int ncand = n_cand_of(sh);
         const int kmax = k_cap < ncand ? k_cap : ncand;
-        return plan_attn(sh, n, kmax + sh->T - ncand * sh->C).ws_bytes;
+        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, kmax + sh->T - ncand * sh->C).ws_bytes;
     }
     case KVEV_OP_DENSE_ATTENTION:
-        return plan_attn(sh, n, sh->T).ws_bytes;
+        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, sh->T).ws_bytes;
     default:
         return 0;
     }

@@ -164,3 +164,37 @@ def test_config4_streaming_full_size_sampled():
     assert du <= SCORE_TOL
     assert np.abs(_gather(st.h, 0, seqs).numpy() - rh).max() <= SCORE_TOL
     assert np.abs(_gather(st.c, 0, seqs).numpy() - rc).max() <= 2 * SCORE_TOL
+
+
+def test_config5_multiquery_full_size_sampled():
+    """batch 64 x 32 heads, T = 32768, C = 64, 256 new-frame queries per sequence (matrix-core
+    attention), LSTM hidden 512: cold step on every sequence, oracle on a sample; the dense
+    baseline is checked on a sample of queries (the oracle needs 2 G multiply-adds per sequence)."""
+    cfg = synth.CONFIGS[5]
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80 << 30:
+        pytest.skip("needs ~45 GB of device memory")
+    w = synth.make_weights(cfg, "cuda")
+    g = synth.make_qkv(cfg, "cuda")
+    st = kb.DecodeState(cfg)
+    O = torch.empty_like(g["Q"])
+    D = torch.empty_like(g["Q"])
+    gw = dict(g)
+    gw.update(w)
+    kb.cold_step(st, gw, O)
+    kb.kvev_dense_attention(st.shape, g["Q"], cfg.Tq, g["K"], g["V"], D, st.ws)
+    torch.cuda.synchronize()
+    print("\n[cfg5] GPU done", flush=True)
+    _select_all(cfg, st, cfg.T)
+    seqs = _sample_slices(cfg, 12, [0])[0]
+    r = _check_layer(cfg, 0, seqs, g, w, st, O, None, cfg.T)
+    print(f"[cfg5] summary flips {r['flips'][0]:.2e} (max {r['flips'][1]:.2f} ulp), max |util-oracle| {r['du']:.2e}",
+          flush=True)
+    assert r["flips"][1] <= 1.01 and r["flips"][0] < 5e-3
+    # dense baseline: 3 sequences x 6 queries
+    sub = [seqs[0], seqs[len(seqs) // 2], seqs[-1]]
+    qsel = torch.tensor([0, 15, 16, 100, 254, 255], device="cuda")
+    K, V = _gather(g["K"], 0, sub), _gather(g["V"], 0, sub)
+    Qs = _gather(g["Q"], 0, sub)[:, :, :, qsel.cpu()].contiguous()
+    rD = orc.dense_attention(Qs, K, V, cfg.T)
+    assert_close_storage(_gather(D, 0, sub)[:, :, :, qsel.cpu()].contiguous(), rD, cfg.dtype, "dense O (sampled queries)")

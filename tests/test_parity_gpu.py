@@ -32,6 +32,10 @@ ATTN_CASES = [
     _cfg(103, "bf16", d=128, T=2077, Tq=1, L=1, B=1, H=2),      # forces a split with a ragged tail
     _cfg(104, "bf16", d=64, T=777, Tq=2),
     _cfg(105, "bf16", d=128, T=5, Tq=1),                          # fewer rows than one lane-group batch
+    _cfg(106, "bf16", d=128, T=1000, Tq=20, L=1, B=2, H=2),       # matrix-core path: ragged query and row tiles
+    _cfg(107, "bf16", d=64, T=333, Tq=130, L=1, B=1, H=3),
+    _cfg(108, "bf16", d=128, T=64, Tq=64, L=2, B=1, H=1),         # exactly one tile each way
+    _cfg(109, "f32", d=64, T=200, Tq=40, L=1, B=1, H=2),          # fp32 storage: many queries on the streaming kernel
 ]
 
 
@@ -60,6 +64,9 @@ GATED_CASES = [
     _cfg(114, "f32", d=128, T=640, C=8, W=0, k=200),             # k > N_cand and no raw window
     _cfg(115, "bf16", d=64, T=4096, C=32, W=256, k=32, L=1, B=1, H=4),
     _cfg(116, "f32", d=64, T=512, C=16, W=64, k=0),              # keep nothing
+    _cfg(117, "bf16", d=128, T=2048, C=32, W=256, k=19, Tq=70, L=1, B=2, H=2),   # matrix-core path, gather + window
+    _cfg(118, "bf16", d=64, T=700, C=16, W=50, k=300, Tq=16, L=1, B=1, H=3),     # k > N_cand, ragged window
+    _cfg(119, "bf16", d=128, T=100, C=32, W=256, k=4, Tq=33, L=1, B=1, H=2),     # no candidate: raw tokens only
 ]
 
 
@@ -87,7 +94,7 @@ def test_gated_attention_teacher_forced(cfg):
 
 
 def test_attention_empty_cases():
-    cfg = _cfg(117, "f32", T=0)
+    cfg = _cfg(129, "f32", T=0)
     t = synth.make_qkv(cfg, "cpu", T_cap=16)
     g = dev(t)
     sh = kb.make_shape(cfg, T=0, T_cap=16, N_cap=1)
