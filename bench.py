@@ -56,6 +56,18 @@ def costs(cfg, T=None):
     }
 
 
+def measured_traffic(workload, stage):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy-kernel reading); kept as data under profiles/ because counters are collected in
+    runs of their own."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(stage)
+    except (OSError, ValueError):
+        return None
+
+
 def roof(name, kernel, cost, us, bound):
     if bound == "hbm":
         ach, peak, unit = cost["bytes"] / us / 1e3, PEAK_HBM_GBS, "GB/s"
@@ -77,6 +89,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the large-launch attention lines (config 3)")
     ap.add_argument("--only", default="", help="profiling aid: run only this stage in the timed loop "
                                                  "(pool|gate|select|attend|dense)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="profiling aid: run 10 plain device copies of 1 GiB and exit (reference reading "
+                         "for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no inter-GPU step); --gpus must be 1",
@@ -92,6 +107,14 @@ def main():
         sys.exit(1)
     kb.lib()
     dev = "cuda"
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_()
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 10}}))
+        return
     cfg = synth.CONFIGS[int(args.workload[3:])]
     cost = costs(cfg)
     S = cfg.L * cfg.B * cfg.H
@@ -170,10 +193,16 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
-    kernels = {"pool": "pool kernel", "gate": "lstm recurrence kernel", "select": "select_kernel",
-               "attend": "attn_decode_kernel", "dense": "attn_decode_kernel"}
+    mfma = cfg.dtype == "bf16"
+    kernels = {"pool": "pool_mfma_kernel" if mfma and cfg.d_sum % 32 == 0 else "pool_generic_kernel",
+               "gate": f"lstm_rec_kernel<{cfg.d_g}>" if mfma and cfg.d_g in (64, 128, 256, 512) else "lstm_generic_kernel",
+               "select": "select_kernel",
+               "attend": "attn_mq_kernel" if mfma and Tq >= 16 else "attn_decode_kernel",
+               "dense": "attn_mq_kernel" if mfma and Tq >= 16 else "attn_decode_kernel"}
     bounds = {"pool": "hbm", "gate": "mfma", "select": "hbm", "attend": "hbm", "dense": "hbm"}
     rooflines = [roof(n, kernels[n], cost[n], stage_us[n], bounds[n]) for n, _ in stages if stage_us[n] > 0]
+    for r in rooflines:
+        r["traffic"] = measured_traffic(cfg.name, r["stage"])
     out = {
         "metric": "gated-chunk decode attn tokens/s per layer", "value": round(value, 2), "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -206,7 +235,37 @@ def main():
                         "hbm_frac": round(cost["dense"]["bytes"] / t_den / 1e3 / PEAK_HBM_GBS, 4),
                         "speedup_steady_vs_dense": round(t_den / t_att, 2),
                         "speedup_cold_step_vs_dense": round(t_den / (ms_per_step * 1e3), 4)}
-        out["rooflines"].append(roof("dense", kernels["dense"], cost["dense"], t_den, "hbm"))
+        rd = roof("dense", kernels["dense"], cost["dense"], t_den, "hbm")
+        rd["traffic"] = measured_traffic(cfg.name, "dense")
+        out["rooflines"].append(rd)
+        # the same steady-state step replayed from a HIP graph (the library neither allocates nor
+        # synchronises, so a caller can capture it): GPU time without the host launch path
+        try:
+            gr = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                attend(sets[0])
+                with torch.cuda.graph(gr, stream=side):
+                    for i in range(R):
+                        attend(sets[i % R])
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            gr.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(5, 200 // R)
+            e0.record()
+            for _ in range(reps):
+                gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t_gr = e0.elapsed_time(e1) * 1e3 / (reps * R)
+            out["steady_state"]["graph_replay_us_per_step"] = round(t_gr, 3)
+            out["steady_state"]["graph_replay_tokens_per_s_per_layer"] = round(cfg.B * Tq * cfg.L / (t_gr * 1e-6), 1)
+            out["steady_state"]["graph_replay_hbm_GBps"] = round(cost["attend"]["bytes"] / t_gr / 1e3, 1)
+        except Exception as ex:  # graph capture is a reporting extra: never fail the bench on it
+            out["steady_state"]["graph_replay_error"] = str(ex)[:200]
 
     # ---- large launch: config 3 attention, layer-batched (the bandwidth-bound regime) ----
     if not args.no_extra and not args.only and args.workload == "cfg2":
