@@ -118,10 +118,10 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
     return sh->dtype == KVEV_BF16 && (sh->d_g == 64 || sh->d_g == 128 || sh->d_g == 256 || sh->d_g == 512);
 }
 
-// W_hh re-laid in MFMA fragment order sits at the front of the scratch.
+// W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch.
 static size_t lstm_ws_pack(const kvev_shape *sh)
 {
-    return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * sh->d_g * 2 : 0;
+    return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 : 0;
 }
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
@@ -207,6 +207,7 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
         a.tb = (int)tb;
         a.whh_packed = static_cast<const bf16x8_t *>(ws);
+        a.wih_packed = a.whh_packed + (size_t)sh->L * 4 * sh->d_g * sh->d_g / 8;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
     } else {

@@ -35,6 +35,7 @@ struct LstmArgs {
     float *h, *c, *util, *gate;
     float *xproj;         // workspace: fp32 input projections of a block of steps (fragment layout)
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *whh_packed;   // workspace: W_hh in fragment order
+    const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *wih_packed;   // workspace: W_ih in fragment order
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block

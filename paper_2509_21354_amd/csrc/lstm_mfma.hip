@@ -43,6 +43,15 @@ __device__ __forceinline__ float tanh_hw(float x)
 
 constexpr int kTT = 4;   // steps per wave pass of the input projection
 
+// Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
+// contiguous run of sequence groups, i.e. a few layers at a time, so that the
+// layer weights a workgroup streams every step stay in that XCD's 4 MB L2
+// instead of all layers cycling through all eight of them.
+__device__ __forceinline__ int xcd_order(int block, int nblocks)
+{
+    return nblocks % 8 == 0 ? (block % 8) * (nblocks / 8) + block / 8 : block;
+}
+
 // Geometry shared by the three kernels: unit tiles per wave, waves per workgroup.
 template <int DG> struct Geo {
     static constexpr int UT = DG == 512 ? 4 : 2;   // keeps the workgroup at 8 waves (256 registers per lane)
@@ -66,7 +75,8 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g4 = lane >> 4;
     const int gpl = (a.BH + 15) / 16;
-    const int l = blockIdx.x / gpl, grp = blockIdx.x % gpl;
+    const int gid = xcd_order(blockIdx.x, gridDim.x);
+    const int l = gid / gpl, grp = gid % gpl;
     const int sl = min(grp * 16 + n, a.BH - 1);
     const size_t s = (size_t)l * a.BH + sl;
     const int tt0 = blockIdx.y * kTT;
@@ -84,7 +94,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
             xb[j][ks] = *reinterpret_cast<const bf16x8_t *>(src);
         }
     }
-    const bf16_t *W = static_cast<const bf16_t *>(a.W_ih) + (size_t)l * 4 * DG * 2 * D;
+    const bf16x8_t *Wp = a.wih_packed + ((size_t)l * Geo<DG>::NW + wave) * UT * 4 * KS * 64 + lane;
     const bf16_t *b_ih = static_cast<const bf16_t *>(a.b_ih) + (size_t)l * 4 * DG;
     const bf16_t *b_hh = static_cast<const bf16_t *>(a.b_hh) + (size_t)l * 4 * DG;
     for (int ut = 0; ut < UT; ++ut) {
@@ -93,8 +103,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
             const int row0 = q * DG + wave * 16 * UT + ut * 16;
             bf16x8_t wf[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                wf[ks] = *reinterpret_cast<const bf16x8_t *>(W + (size_t)(row0 + n) * 2 * D + ks * 32 + g4 * 8);
+            for (int ks = 0; ks < KS; ++ks) wf[ks] = Wp[(((size_t)ut * 4 + q) * KS + ks) * 64];
             float bias[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -107,7 +116,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], xb[j][ks], acc, 0, 0, 0);
                 if (tt0 + j < nb) {
                     float4 o = make_float4(acc[0] + bias[0], acc[1] + bias[1], acc[2] + bias[2], acc[3] + bias[3]);
-                    float *dst = a.xproj + xp_block<DG>(blockIdx.x, a.tb, tt0 + j, wave, ut, q) * 256 + lane * 4;
+                    float *dst = a.xproj + xp_block<DG>(gid, a.tb, tt0 + j, wave, ut, q) * 256 + lane * 4;
                     *reinterpret_cast<float4 *>(dst) = o;
                 }
             }
@@ -137,6 +146,26 @@ __global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, 
     packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
 }
 
+// W_ih in A-fragment order for the input projection: [layer][wave][unit tile][gate][k-step][lane][8].
+template <int DG, int D>
+__global__ __launch_bounds__(256) void lstm_pack_wih_kernel(const bf16_t *W_ih, bf16x8_t *packed, int L)
+{
+    constexpr int NW = Geo<DG>::NW, UT = Geo<DG>::UT, KS = 2 * D / 32;
+    const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)L * NW * UT * 4 * KS * 64;
+    if (frag >= total) return;
+    const int lane = frag % 64;
+    size_t r = frag / 64;
+    const int ks = r % KS; r /= KS;
+    const int q = r % 4; r /= 4;
+    const int ut = r % UT; r /= UT;
+    const int wave = r % NW;
+    const int l = (int)(r / NW);
+    const int n = lane & 15, g4 = lane >> 4;
+    const bf16_t *src = W_ih + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * 2 * D + ks * 32 + g4 * 8;
+    packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
+}
+
 template <int DG>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, int t0, int nb)
 {
@@ -159,7 +188,8 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
     const int gpl = (a.BH + 15) / 16;
-    const int l = blockIdx.x / gpl, grp = blockIdx.x % gpl;
+    const int gid = xcd_order(blockIdx.x, gridDim.x);
+    const int l = gid / gpl, grp = gid % gpl;
     const bool live = grp * 16 + n < a.BH;
     const size_t s = (size_t)l * a.BH + min(grp * 16 + n, a.BH - 1);
 
@@ -181,7 +211,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
     // this wave's packed A fragments: fragment (item, q) of this lane sits at wp[(item*4 + q)*64]
     const unsigned char *wbase = reinterpret_cast<const unsigned char *>(a.whh_packed + ((size_t)l * NW + wave) * KS * UT * 4 * 64);
     const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
-        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(blockIdx.x, a.tb, 0, wave, 0, 0) * 64);
+        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(gid, a.tb, 0, wave, 0, 0) * 64);
     const uint32_t lane16 = lane * 16;
     bf16_t *h_wr = s_h + (size_t)n * HP + wave * 16 * UT + 4 * g4;          // + (buf*3+p)*16*HP + ut*16
     const bf16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;                // + (buf*3+p)*16*HP + ks*32
@@ -307,6 +337,13 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         const size_t frags = (size_t)a.L * 4 * DG * DG / 8;
         hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
                            static_cast<const bf16_t *>(a.W_hh), const_cast<bf16x8_t *>(a.whh_packed), a.L);
+        const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
+        if (a.d == 64)
+            hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 64>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
+                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L);
+        else
+            hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 128>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
+                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L);
     }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;

@@ -11,7 +11,8 @@
 //      rows as the A operand (read from global memory; the four weight
 //      matrices total 128 KiB and stay in cache) and the 16 tile rows as B.
 // The fp32 means and activations are fed to the bf16 matrix cores as three
-// bf16 terms each (x = hi + mid + lo, exact to 24 bits): weights are bf16, so
+// bf16 terms each (x = hi + mid + lo, exact to 24 bits; cut once, when the value
+// is written to LDS, into three bf16 planes): weights are bf16, so
 // every partial product is exact and the fp32 accumulation gives fp32-grade
 // results, which is what keeps the stored summaries equal to a double
 // precision evaluation except for rare last-bit flips.
@@ -20,38 +21,24 @@
 
 namespace kvev {
 
-struct Split3 { bf16x8_t hi, mid, lo; };
-
-// 8 fp32 -> three bf16x8 terms whose sum is the input (to 24 bits)
-__device__ __forceinline__ Split3 split3(const float (&x)[8])
+// two fp32 -> three packed bf16 pairs whose sums are the inputs (to 24 bits)
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t &hi, uint32_t &mid, uint32_t &lo)
 {
-    uint32_t h[4], m[4], l[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        h[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
-        const float r0 = x[2 * i] - __uint_as_float(h[i] << 16);
-        const float r1 = x[2 * i + 1] - __uint_as_float(h[i] & 0xFFFF0000u);
-        m[i] = pack_bf16x2(r0, r1);
-        const float s0 = r0 - __uint_as_float(m[i] << 16);
-        const float s1 = r1 - __uint_as_float(m[i] & 0xFFFF0000u);
-        l[i] = pack_bf16x2(s0, s1);
-    }
-    Split3 o;
-    o.hi = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
-    o.mid = __builtin_bit_cast(bf16x8_t, make_uint4(m[0], m[1], m[2], m[3]));
-    o.lo = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
-    return o;
+    hi = pack_bf16x2(x0, x1);
+    const float r0 = x0 - __uint_as_float(hi << 16), r1 = x1 - __uint_as_float(hi & 0xFFFF0000u);
+    mid = pack_bf16x2(r0, r1);
+    lo = pack_bf16x2(r0 - __uint_as_float(mid << 16), r1 - __uint_as_float(mid & 0xFFFF0000u));
 }
 
 template <int D>
 __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
 {
     constexpr int EPL = D / 16;          // elements per lane of a 16-lane row group
-    constexpr int XP = D + 4;            // padded fp32 row of the mean tile
-    extern __shared__ __align__(16) float smem[];
-    float *xm = smem;                    // [2][16][XP]   chunk means (K then V)
-    float *act = smem + 2 * 16 * XP;     // [2][16][d_sum + 4]
-    const int AP = a.d_sum + 4;
+    constexpr int XP = D + 8;            // padded bf16 row of a mean plane
+    extern __shared__ __align__(16) bf16_t smem[];
+    bf16_t *xm = smem;                   // [3 terms][2 (K,V)][16 rows][XP]   chunk means
+    const int AP = a.d_sum + 8;
+    bf16_t *act = smem + 3 * 2 * 16 * XP;   // [3][2][16][AP]   hidden activations
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g4 = lane >> 4;
@@ -102,9 +89,16 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
         }
         if (g4 == 0) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                xm[(0 * 16 + rt) * XP + n * EPL + e] = sk[e] / cf;
-                xm[(1 * 16 + rt) * XP + n * EPL + e] = sv[e] / cf;
+            for (int e = 0; e < EPL; e += 2) {
+                uint32_t hi, mid, lo;
+                split3_pair(sk[e] / cf, sk[e + 1] / cf, hi, mid, lo);
+                *reinterpret_cast<uint32_t *>(xm + ((0 * 2 + 0) * 16 + rt) * XP + n * EPL + e) = hi;
+                *reinterpret_cast<uint32_t *>(xm + ((1 * 2 + 0) * 16 + rt) * XP + n * EPL + e) = mid;
+                *reinterpret_cast<uint32_t *>(xm + ((2 * 2 + 0) * 16 + rt) * XP + n * EPL + e) = lo;
+                split3_pair(sv[e] / cf, sv[e + 1] / cf, hi, mid, lo);
+                *reinterpret_cast<uint32_t *>(xm + ((0 * 2 + 1) * 16 + rt) * XP + n * EPL + e) = hi;
+                *reinterpret_cast<uint32_t *>(xm + ((1 * 2 + 1) * 16 + rt) * XP + n * EPL + e) = mid;
+                *reinterpret_cast<uint32_t *>(xm + ((2 * 2 + 1) * 16 + rt) * XP + n * EPL + e) = lo;
             }
         }
     }
@@ -123,8 +117,14 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
             const int r = row0 + rt;
             if (r < rows_per_layer) {
                 const size_t o = (((size_t)l * a.BH + r / nch) * a.N_cap + (a.c0 + r % nch)) * D + e;
-                *reinterpret_cast<uint32_t *>((kv ? Vb : Kb) + o) =
-                    pack_bf16x2(xm[(kv * 16 + rt) * XP + e], xm[(kv * 16 + rt) * XP + e + 1]);
+                float m0 = 0.f, m1 = 0.f;      // lo + mid + hi is exact: each partial sum is a prefix of the fp32 mean
+#pragma unroll
+                for (int p = 2; p >= 0; --p) {
+                    const uint32_t w = *reinterpret_cast<const uint32_t *>(xm + ((p * 2 + kv) * 16 + rt) * XP + e);
+                    m0 += __uint_as_float(w << 16);
+                    m1 += __uint_as_float(w & 0xFFFF0000u);
+                }
+                *reinterpret_cast<uint32_t *>((kv ? Vb : Kb) + o) = pack_bf16x2(m0, m1);
             }
         }
         return;
@@ -143,18 +143,19 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
 #pragma unroll
         for (int ks = 0; ks < D / 32; ++ks) {
             const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W1 + ks * 32);
-            float x[8];
-            const float *xr = xm + (kv * 16 + n) * XP + ks * 32 + g4 * 8;
-            const float4 x0 = *reinterpret_cast<const float4 *>(xr), x1 = *reinterpret_cast<const float4 *>(xr + 4);
-            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-            const Split3 sp = split3(x);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.lo, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.mid, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.hi, acc, 0, 0, 0);
+#pragma unroll
+            for (int p = 2; p >= 0; --p) {
+                const bf16x8_t x = *reinterpret_cast<const bf16x8_t *>(xm + ((p * 2 + kv) * 16 + n) * XP + ks * 32 + g4 * 8);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, x, acc, 0, 0, 0);
+            }
         }
-        float4 g;
-        g.x = gelu_erf(acc[0]); g.y = gelu_erf(acc[1]); g.z = gelu_erf(acc[2]); g.w = gelu_erf(acc[3]);
-        *reinterpret_cast<float4 *>(act + (kv * 16 + n) * AP + u0 + 4 * g4) = g;
+        uint32_t hi[2], mid[2], lo[2];
+        split3_pair(gelu_erf(acc[0]), gelu_erf(acc[1]), hi[0], mid[0], lo[0]);
+        split3_pair(gelu_erf(acc[2]), gelu_erf(acc[3]), hi[1], mid[1], lo[1]);
+        bf16_t *ap = act + (size_t)(kv * 16 + n) * AP + u0 + 4 * g4;
+        *reinterpret_cast<uint2 *>(ap + (size_t)0 * 2 * 16 * AP) = make_uint2(hi[0], hi[1]);
+        *reinterpret_cast<uint2 *>(ap + (size_t)1 * 2 * 16 * AP) = make_uint2(mid[0], mid[1]);
+        *reinterpret_cast<uint2 *>(ap + (size_t)2 * 2 * 16 * AP) = make_uint2(lo[0], lo[1]);
     }
     __syncthreads();
 
@@ -169,14 +170,11 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
         for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b2[r]);
         for (int ks = 0; ks < ds / 32; ++ks) {
             const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W2 + ks * 32);
-            float x[8];
-            const float *xr = act + (kv * 16 + n) * AP + ks * 32 + g4 * 8;
-            const float4 x0 = *reinterpret_cast<const float4 *>(xr), x1 = *reinterpret_cast<const float4 *>(xr + 4);
-            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-            const Split3 sp = split3(x);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.lo, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.mid, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, sp.hi, acc, 0, 0, 0);
+#pragma unroll
+            for (int p = 2; p >= 0; --p) {
+                const bf16x8_t x = *reinterpret_cast<const bf16x8_t *>(act + ((size_t)(p * 2 + kv) * 16 + n) * AP + ks * 32 + g4 * 8);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, x, acc, 0, 0, 0);
+            }
         }
         if (live) {
             uint2 o;
@@ -193,7 +191,7 @@ hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st)
     const size_t rows_per_layer = (size_t)a.BH * nch;
     const size_t blocks = (size_t)a.L * ((rows_per_layer + 15) / 16);
     if (blocks == 0) return hipSuccess;
-    const size_t lds = sizeof(float) * (2 * 16 * ((size_t)a.d + 4) + 2 * 16 * ((size_t)a.d_sum + 4));
+    const size_t lds = sizeof(bf16_t) * 3 * 2 * 16 * (((size_t)a.d + 8) + ((size_t)a.d_sum + 8));
     if (a.d == 64)
         hipLaunchKernelGGL((pool_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), lds, st, a);
     else
