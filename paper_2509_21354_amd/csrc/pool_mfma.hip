@@ -71,15 +71,17 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
                 xk[u].load(K + off);
                 xv[u].load(V + off);
             }
+            // branch-free tail: a row past the chunk was loaded from the last row and gets weight 0
+            // (x * 1 + s rounds as x + s), so every load of the group is in flight before the first use
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (ok[u]) {
-                    float fk[EPL], fv[EPL];
-                    xk[u].get(fk);
-                    xv[u].get(fv);
+            for (int u = 0; u < 8; ++u) {
+                const float wgt = ok[u] ? 1.f : 0.f;
+                float fk[EPL], fv[EPL];
+                xk[u].get(fk);
+                xv[u].get(fv);
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) { sk[e] += fk[e]; sv[e] += fv[e]; }
-                }
+                for (int e = 0; e < EPL; ++e) { sk[e] = fmaf(fk[e], wgt, sk[e]); sv[e] = fmaf(fv[e], wgt, sv[e]); }
+            }
         }
         const float cf = (float)a.C;
 #pragma unroll
