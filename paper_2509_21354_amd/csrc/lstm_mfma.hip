@@ -24,6 +24,8 @@
 // is accumulated in fp32, so the result has fp32 accuracy.
 #include "common.hpp"
 #include "kernels.hpp"
+#include <utility>
+
 
 namespace kvev {
 
@@ -41,6 +43,21 @@ __device__ __forceinline__ float tanh_hw(float x)
     return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
 }
 
+// 16-byte load through a buffer descriptor: address = descriptor base (SGPRs) +
+// voff (one VGPR, shared by every load of the lane) + soff (SGPR or constant),
+// with the constant part of voff folded into the instruction's immediate.  Keeps
+// the many weight-fragment addresses of the recurrence out of the vector registers.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00027000);
+}
+template <typename V> __device__ __forceinline__ V buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff)
+{
+    const u32x4_t raw = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, (int)soff, 0);
+    return __builtin_bit_cast(V, raw);
+}
+
 constexpr int kTT = 4;   // steps per wave pass of the input projection
 
 // Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
@@ -52,13 +69,65 @@ __device__ __forceinline__ int xcd_order(int block, int nblocks)
     return nblocks % 8 == 0 ? (block % 8) * (nblocks / 8) + block / 8 : block;
 }
 
-// Geometry shared by the three kernels: unit tiles per wave, waves per workgroup.
+// Geometry shared by the three kernels: unit tiles per wave, waves per workgroup,
+// and the order in which a wave walks its ITEMS = UT*KS weight items per step (an
+// item = the 4 gate fragments of one unit tile at one k-step, 4 KiB per wave): one
+// unit tile after the other, so that only 4 accumulators are live and the cell
+// update of a finished tile overlaps with the other waves' MFMAs.
 template <int DG> struct Geo {
     static constexpr int UT = DG == 512 ? 4 : 2;   // keeps the workgroup at 8 waves (256 registers per lane)
     static constexpr int NW = DG / (16 * UT);
     static constexpr int KS = DG / 32;
     static constexpr int THREADS = NW * 64;
+    static constexpr int ITEMS = UT * KS;
+    static constexpr int ut_of(int i) { return i / KS; }
+    static constexpr int ks_of(int i) { return i % KS; }
 };
+
+// Where the weight items of the recurrence live.  A CU pulls at most 64 bytes per
+// clock out of L2, which for d_g = 256 (512 KiB of W_hh per step) is longer than
+// the step's MFMA time, so part of the stream stays on chip: class 0 items sit in
+// LDS, class 1 items in registers, and only class 2 items are streamed from L2
+// every step, through a ring of NSLOT register buffers.  d_g <= 128 keeps the
+// whole matrix in LDS; d_g = 512 has room for neither.  Resident items are spread
+// over the step so that the streamed ones arrive at an even pace.
+template <int DG> struct Res {
+    using G = Geo<DG>;
+    static constexpr int ITEMS = G::ITEMS;
+    static constexpr int cls(int i)
+    {
+        if (DG <= 128) return 0;
+        if (DG == 256) return i % 2 != 0 ? 2 : i % 6 == 0 ? 0 : 1;     // of 16: 3 in LDS, 5 in registers, 8 streamed
+        return 2;
+    }
+    static constexpr int count(int c) { int k = 0; for (int i = 0; i < ITEMS; ++i) k += cls(i) == c; return k; }
+    static constexpr int idx(int i) { int k = 0; for (int j = 0; j < i; ++j) k += cls(j) == cls(i); return k; }   // rank within its class
+    static constexpr int pos(int c, int k) { for (int i = 0; i < ITEMS; ++i) if (cls(i) == c && idx(i) == k) return i; return 0; }
+    static constexpr int LRES = count(0), RRES = count(1), NS = count(2);
+    static constexpr int NSLOT = NS == 0 ? 1 : DG == 256 ? 4 : 8;
+    static constexpr int PF = NSLOT - 1;
+    static_assert(NS % NSLOT == 0, "slot rotation must line up with the item loop");
+    // register buffers for LDS items, read one item ahead: two when LDS items follow each other
+    static constexpr bool lds_adjacent() { for (int i = 0; i < ITEMS; ++i) if (cls(i) == 0 && cls((i + 1) % ITEMS) == 0) return true; return false; }
+    static constexpr int NWL = lds_adjacent() ? 2 : 1;
+    static_assert(NWL == 1 || LRES % 2 == 0, "buffer parity must survive the wrap into the next step");
+    static constexpr size_t lds_h = (size_t)2 * 3 * 16 * (DG + 8) * sizeof(bf16_t);
+    static constexpr size_t lds_up = (size_t)2 * G::NW * 16 * sizeof(float);
+    static constexpr size_t lds_w = (size_t)G::NW * LRES * 4096;
+    static constexpr size_t lds = lds_h + lds_up + lds_w;
+    static_assert(lds <= 160 * 1024, "LDS budget of a CU");
+};
+
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // Scratch layout: 1 KiB blocks of 64 lanes x 4 floats, one per
 // (sequence group, step of the block, wave, unit tile, gate).
@@ -126,19 +195,21 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
 
 // W_hh re-laid in A-fragment order so that every wave-level load of the
 // recurrence is one contiguous 1 KiB piece (the row-major matrix would give 16
-// half-used cache lines per load): [layer][wave][unit tile][k-step][gate][lane][8].
+// half-used cache lines per load): [layer][wave][item][gate][lane][8], items in
+// the order the wave walks them.
 template <int DG>
 __global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, bf16x8_t *packed, int L)
 {
-    constexpr int NW = Geo<DG>::NW, KS = Geo<DG>::KS, UT = Geo<DG>::UT;
+    using G = Geo<DG>;
+    constexpr int NW = G::NW, UT = G::UT;
     const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;         // one 16-byte fragment per thread
-    const size_t total = (size_t)L * NW * KS * UT * 4 * 64;
+    const size_t total = (size_t)L * NW * G::ITEMS * 4 * 64;
     if (frag >= total) return;
     const int lane = frag % 64;
     size_t r = frag / 64;
     const int q = r % 4; r /= 4;
-    const int ks = r % KS; r /= KS;
-    const int ut = r % UT; r /= UT;
+    const int item = r % G::ITEMS; r /= G::ITEMS;
+    const int ut = G::ut_of(item), ks = G::ks_of(item);
     const int wave = r % NW;
     const int l = (int)(r / NW);
     const int n = lane & 15, g4 = lane >> 4;
@@ -169,19 +240,14 @@ __global__ __launch_bounds__(256) void lstm_pack_wih_kernel(const bf16_t *W_ih, 
 template <int DG>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, int t0, int nb)
 {
-    constexpr int NW = Geo<DG>::NW, KS = Geo<DG>::KS, UT = Geo<DG>::UT, HP = DG + 8;
-    // The weight fragments of a wave form one stream of ITEMS = UT*KS items (4
-    // fragments each: gates i,f,g,o of one unit tile at one k-step), read from L2
-    // through a ring of NSLOT register buffers that runs NSLOT-1 items ahead of the
-    // MFMAs and wraps into the next time step, so the cell update and the barrier
-    // overlap with loads already in flight.
-    constexpr int ITEMS = UT * KS;
-    constexpr int NSLOT = (Geo<DG>::THREADS >= 1024 || ITEMS < 8) ? 4 : 8;
-    constexpr int PF = NSLOT - 1;
-    static_assert(ITEMS % NSLOT == 0, "slot rotation must line up with the item loop");
+    using G = Geo<DG>;
+    using R = Res<DG>;
+    constexpr int NW = G::NW, KS = G::KS, UT = G::UT, ITEMS = G::ITEMS, HP = DG + 8;
+    constexpr int LRES = R::LRES, RRES = R::RRES, NS = R::NS, NSLOT = R::NSLOT, PF = R::PF, NWL = R::NWL;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t *s_h = reinterpret_cast<bf16_t *>(smem_raw);                                   // [2][3][16][HP]
-    float *s_up = reinterpret_cast<float *>(smem_raw + (size_t)2 * 3 * 16 * HP * sizeof(bf16_t));   // [2][NW][16]
+    float *s_up = reinterpret_cast<float *>(smem_raw + R::lds_h);                         // [2][NW][16]
+    unsigned char *s_w = smem_raw + R::lds_h + R::lds_up;                                 // [NW][LRES] items of 4 KiB
 
     // wave index as a scalar, so that per-wave base addresses live in SGPRs and every
     // fragment load is (scalar base) + (one lane-offset VGPR) + (immediate)
@@ -208,90 +274,138 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
             ws_reg[ut][r] = bf16_to_f32(w_s[unit]);
         }
 
-    // this wave's packed A fragments: fragment (item, q) of this lane sits at wp[(item*4 + q)*64]
-    const unsigned char *wbase = reinterpret_cast<const unsigned char *>(a.whh_packed + ((size_t)l * NW + wave) * KS * UT * 4 * 64);
+    // this wave's packed A fragments: fragment q of item i of this lane sits at wbase + i*4096 + q*1024 + lane*16
+    const unsigned char *wbase = reinterpret_cast<const unsigned char *>(a.whh_packed + ((size_t)l * NW + wave) * ITEMS * 4 * 64);
     const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
         reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(gid, a.tb, 0, wave, 0, 0) * 64);
     const uint32_t lane16 = lane * 16;
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wbase, ITEMS * 4096);
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * NW * UT * 4096 - (uint32_t)wave * UT * 4096);
     bf16_t *h_wr = s_h + (size_t)n * HP + wave * 16 * UT + 4 * g4;          // + (buf*3+p)*16*HP + ut*16
     const bf16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;                // + (buf*3+p)*16*HP + ks*32
+    unsigned char *w_lds = s_w + (size_t)wave * LRES * 4096 + lane16;  // + k*4096 + q*1024 for the wave's k-th LDS item
 
-    auto publish_h = [&](int buf, int ut) {
-        {
-            float hi[4], mid[4], lo[4];
+    auto publish_h = [&](int buf, int ut, const float (&hv)[4]) {
+        float hi[4], mid[4], lo[4];
 #pragma unroll
-            for (int r = 0; r < 4; r += 2) {
-                const uint32_t ph = pack_bf16x2(h_reg[ut][r], h_reg[ut][r + 1]);
-                hi[r] = __uint_as_float(ph << 16); hi[r + 1] = __uint_as_float(ph & 0xFFFF0000u);
-                const float r0 = h_reg[ut][r] - hi[r], r1 = h_reg[ut][r + 1] - hi[r + 1];
-                const uint32_t pm = pack_bf16x2(r0, r1);
-                mid[r] = __uint_as_float(pm << 16); mid[r + 1] = __uint_as_float(pm & 0xFFFF0000u);
-                lo[r] = r0 - mid[r]; lo[r + 1] = r1 - mid[r + 1];
-            }
-            uint2 v;
-            v.x = pack_bf16x2(hi[0], hi[1]); v.y = pack_bf16x2(hi[2], hi[3]);
-            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 0) * 16 * HP + ut * 16) = v;
-            v.x = pack_bf16x2(mid[0], mid[1]); v.y = pack_bf16x2(mid[2], mid[3]);
-            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 1) * 16 * HP + ut * 16) = v;
-            v.x = pack_bf16x2(lo[0], lo[1]); v.y = pack_bf16x2(lo[2], lo[3]);
-            *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 2) * 16 * HP + ut * 16) = v;
+        for (int r = 0; r < 4; r += 2) {
+            const uint32_t ph = pack_bf16x2(hv[r], hv[r + 1]);
+            hi[r] = __uint_as_float(ph << 16); hi[r + 1] = __uint_as_float(ph & 0xFFFF0000u);
+            const float r0 = hv[r] - hi[r], r1 = hv[r + 1] - hi[r + 1];
+            const uint32_t pm = pack_bf16x2(r0, r1);
+            mid[r] = __uint_as_float(pm << 16); mid[r + 1] = __uint_as_float(pm & 0xFFFF0000u);
+            lo[r] = r0 - mid[r]; lo[r + 1] = r1 - mid[r + 1];
         }
+        uint2 v;
+        v.x = pack_bf16x2(hi[0], hi[1]); v.y = pack_bf16x2(hi[2], hi[3]);
+        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 0) * 16 * HP + ut * 16) = v;
+        v.x = pack_bf16x2(mid[0], mid[1]); v.y = pack_bf16x2(mid[2], mid[3]);
+        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 1) * 16 * HP + ut * 16) = v;
+        v.x = pack_bf16x2(lo[0], lo[1]); v.y = pack_bf16x2(lo[2], lo[3]);
+        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 2) * 16 * HP + ut * 16) = v;
     };
 
-    bf16x8_t wbuf[NSLOT][4];
-    auto load_w = [&](int slot, int item) {
+    // ---- resident items: LDS and registers, filled once ------------------------
+    static_for<LRES>([&](auto kc) {
+        constexpr int k = decltype(kc)::value, i = R::pos(0, k);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            wbuf[slot][q] = *reinterpret_cast<const bf16x8_t *>(wbase + (size_t)item * 4096 + (lane16 + q * 1024));
+            *reinterpret_cast<bf16x8_t *>(w_lds + k * 4096 + q * 1024) = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
+    });
+    bf16x8_t wres[RRES > 0 ? RRES : 1][4];
+    static_for<RRES>([&](auto kc) {
+        constexpr int k = decltype(kc)::value, i = R::pos(1, k);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wres[k][q] = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
+    });
+    // ---- streamed items: the ring runs PF items ahead and wraps into the next step,
+    // so the cell update and the barrier overlap with loads already in flight ----
+    bf16x8_t wbuf[NSLOT][4];
+    auto load_w = [&](auto jc) {               // jc: index within the streamed items
+        constexpr int j = decltype(jc)::value, i = R::pos(2, j);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wbuf[j % NSLOT][q] = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
     };
+    if constexpr (NS > 0) static_for<PF>(load_w);
+    // LDS items pass through a register buffer that is read one item ahead
+    bf16x8_t wl[NWL][4];
+    auto read_wl = [&](auto kc) {              // kc: index within the LDS items
+        constexpr int k = decltype(kc)::value;
 #pragma unroll
-    for (int i = 0; i < PF; ++i) load_w(i, i);
+        for (int q = 0; q < 4; ++q) wl[k % NWL][q] = *reinterpret_cast<const bf16x8_t *>(w_lds + k * 4096 + q * 1024);
+    };
+    // the three bf16 planes of h for one k-step, read one group of items ahead
+    bf16x8_t hb[2][3];
+    auto read_h = [&](bf16x8_t (&dst)[3], int buf, int ks) {
 #pragma unroll
-    for (int ut = 0; ut < UT; ++ut) publish_h(0, ut);
-    __syncthreads();
+        for (int p = 0; p < 3; ++p)
+            dst[p] = *reinterpret_cast<const bf16x8_t *>(h_rd + (size_t)(buf * 3 + p) * 16 * HP + ks * 32);
+    };
+
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) publish_h(0, ut, h_reg[ut]);
+    __syncthreads();             // h of step t0 - 1 and the LDS items are in place
+    if constexpr (R::cls(0) == 0) read_wl(std::integral_constant<int, 0>{});
 
     for (int tt = 0; tt < nb; ++tt) {
         const int cur = tt & 1, nxt = cur ^ 1;
         float upart = 0.f;
-#pragma unroll
-        for (int ut = 0; ut < UT; ++ut) {
-            // the accumulators start from the step's input projection (read back in the
-            // C-fragment layout it was written in), so the MFMA chain adds W_hh h on top
-            f32x4_t acc[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                acc[q] = *reinterpret_cast<const f32x4_t *>(xbase + ((size_t)tt * NW * UT + ut) * 4096 + (lane16 + q * 1024));
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int item = ut * KS + ks;
-                load_w((item + PF) % NSLOT, (item + PF) % ITEMS);
-                bf16x8_t hb[3];
-#pragma unroll
-                for (int p = 0; p < 3; ++p)
-                    hb[p] = *reinterpret_cast<const bf16x8_t *>(h_rd + (size_t)(cur * 3 + p) * 16 * HP + ks * 32);
-#pragma unroll
-                for (int p = 2; p >= 0; --p)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wbuf[item % NSLOT][q], hb[p], acc[q], 0, 0, 0);
-                // the prefetch depth is the ring, not whatever the scheduler can hoist
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        read_h(hb[0], cur, 0);
+        // The step's input projection (read back in the C-fragment layout it was written
+        // in) is asked for now and added after the MFMA chain, which hides its latency.
+        f32x4_t acc[4], xin[4];
+        auto cell_update = [&](auto utc) {
+            constexpr int ut = decltype(utc)::value;
+            float hv[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float ig = sigmoid_hw(acc[0][r]);
-                const float fg = sigmoid_hw(acc[1][r]);
-                const float gg = tanh_hw(acc[2][r]);
-                const float og = sigmoid_hw(acc[3][r]);
+                const float ig = sigmoid_hw(acc[0][r] + xin[0][r]);
+                const float fg = sigmoid_hw(acc[1][r] + xin[1][r]);
+                const float gg = tanh_hw(acc[2][r] + xin[2][r]);
+                const float og = sigmoid_hw(acc[3][r] + xin[3][r]);
                 const float cn = fmaf(fg, c_reg[ut][r], ig * gg);
                 c_reg[ut][r] = cn;
                 float hn = og * tanh_hw(cn);
                 asm volatile("" : "+v"(hn));     // opaque to the optimiser: hn is the rounded product from here on
-                h_reg[ut][r] = hn;
+                hv[r] = hn;
                 upart = fmaf(ws_reg[ut][r], hn, upart);
             }
-            publish_h(nxt, ut);
-        }
+            publish_h(nxt, ut, hv);
+            if (tt == nb - 1 && live) {          // the state leaves the kernel as fp32
+                const int unit = wave * 16 * UT + ut * 16 + 4 * g4;
+                *reinterpret_cast<float4 *>(a.h + s * DG + unit) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+            }
+        };
+        static_for<ITEMS>([&](auto ic) {
+            constexpr int i = decltype(ic)::value, ut = G::ut_of(i), ks = G::ks_of(i);
+            constexpr int c = R::cls(i), k = R::idx(i);
+            if constexpr (ks == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    xin[q] = buffer_load16<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)(tt * NW * UT + ut) * 4096);
+                    acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+            // operands of what comes next are asked for before this item's MFMAs
+            if constexpr (i + 1 < ITEMS) read_h(hb[(i + 1) & 1], cur, G::ks_of(i + 1));
+            if constexpr (R::cls((i + 1) % ITEMS) == 0) read_wl(std::integral_constant<int, R::idx((i + 1) % ITEMS)>{});
+            if constexpr (c == 2) load_w(std::integral_constant<int, (k + PF) % NS>{});
+            auto chain = [&](const bf16x8_t (&wf)[4]) {
+#pragma unroll
+                for (int p = 2; p >= 0; --p)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q], hb[i & 1][p], acc[q], 0, 0, 0);
+            };
+            if constexpr (c == 0) chain(wl[k % NWL]);
+            else if constexpr (c == 1) chain(wres[k]);
+            else chain(wbuf[k % NSLOT]);
+            // the prefetch depths are the ones written here, not whatever the scheduler can hoist
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (ks == KS - 1) cell_update(std::integral_constant<int, ut>{});
+        });
         upart += __shfl_xor(upart, 16);
         upart += __shfl_xor(upart, 32);
         if (g4 == 0) s_up[(cur * NW + wave) * 16 + n] = upart;
@@ -315,7 +429,6 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
             for (int r = 0; r < 4; ++r) {
                 const int unit = wave * 16 * UT + ut * 16 + 4 * g4 + r;
                 a.c[s * DG + unit] = c_reg[ut][r];
-                a.h[s * DG + unit] = h_reg[ut][r];
             }
     }
 }
@@ -325,7 +438,7 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
 {
     const int gpl = (a.BH + 15) / 16;
     const unsigned groups = (unsigned)(a.L * gpl);
-    const size_t lds = (size_t)2 * 3 * 16 * (DG + 8) * sizeof(bf16_t) + (size_t)2 * Geo<DG>::NW * 16 * sizeof(float);
+    const size_t lds = Res<DG>::lds;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_kernel<DG>),

@@ -195,6 +195,8 @@ LSTM_CASES = [
     _cfg(143, "bf16", d=128, T=1280, C=32, d_g=256, L=2, B=1, H=5),      # 5 sequences per layer: ragged tile
     _cfg(144, "bf16", d=64, T=640, C=32, d_g=64, L=1, B=3, H=7),
     _cfg(145, "bf16", d=128, T=320, C=32, d_g=40),                        # d_g the MFMA tiling does not take
+    _cfg(146, "bf16", d=128, T=768, C=32, d_g=512, L=1, B=1, H=3),        # widest gate: unit tiles one after the other
+    _cfg(147, "bf16", d=64, T=576, C=16, d_g=128, L=2, B=2, H=9),         # W_hh fully resident on chip
 ]
 
 
