@@ -37,7 +37,7 @@
 
 enum { KVO_F32 = 0, KVO_BF16 = 1 };
 enum { KVO_OK = 0, KVO_BAD_ARG = 1 };
-enum { KVO_POOL_MEAN = 0, KVO_POOL_MLP = 1 };
+enum { KVO_POOL_MEAN = 0, KVO_POOL_MLP = 1, KVO_POOL_MAX = 2 };
 
 /* ---------- storage <-> double ------------------------------------------- */
 
@@ -98,7 +98,9 @@ double kvo_gelu(double x) { return gelu(x); }
 /* ---------- pool: Eq. 2 ---------------------------------------------------
  * Reading: a chunk (a set of C vectors) enters the d -> d_sum -> d MLP through
  * its arithmetic mean; MLP_K and MLP_V have separate weights; weights are per
- * layer, shared by batch rows and heads.  Mode MEAN stops after the mean.
+ * layer, shared by batch rows and heads.  Mode MEAN stops after the mean;
+ * mode MAX (one of the alternative aggregators section 3 names, "pooling")
+ * takes the element-wise maximum of the chunk instead, no weights.
  *   K, V        [L,B,H,T_cap,d]       Kbar, Vbar [L,B,H,N_cap,d]
  *   W1 [L,d_sum,d] b1 [L,d_sum] W2 [L,d,d_sum] b2 [L,d]     (row-major out x in)
  * Writes summary rows [c0, c1); needs 0 <= c0 <= c1 <= floor(T/C) <= N_cap.
@@ -109,6 +111,17 @@ static void pool_one(int dtype, int d, int C, int d_sum, int mode,
                      const void *W2, size_t w2_off, const void *b2, size_t b2_off,
                      void *Y, size_t y_off, double *mean, double *act)
 {
+    if (mode == KVO_POOL_MAX) {             /* the "pooling" alternative of section 3: element-wise maximum */
+        for (int e = 0; e < d; ++e) {
+            double m = ld(X, dtype, x_off + e);
+            for (int j = 1; j < C; ++j) {
+                double x = ld(X, dtype, x_off + (size_t)j * d + e);
+                if (x > m) m = x;
+            }
+            st(Y, dtype, y_off + e, m);
+        }
+        return;
+    }
     for (int e = 0; e < d; ++e) {
         double s = 0.0;
         for (int j = 0; j < C; ++j)

@@ -144,7 +144,7 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     (void)ws; (void)ws_bytes;
     int rc = check_shape(sh);
     if (rc) return rc;
-    if (pool_mode != KVEV_POOL_MEAN && pool_mode != KVEV_POOL_MLP) return KVEV_ERR_UNSUPPORTED;
+    if (pool_mode != KVEV_POOL_MEAN && pool_mode != KVEV_POOL_MLP && pool_mode != KVEV_POOL_MAX) return KVEV_ERR_UNSUPPORTED;
     if (!K || !V || !Kbar || !Vbar || !aligned16(K) || !aligned16(V) || !aligned16(Kbar) || !aligned16(Vbar))
         return KVEV_ERR_INVALID_ARG;
     if (chunk_begin < 0 || chunk_begin > chunk_end || chunk_end > sh->T / sh->C) return KVEV_ERR_INVALID_ARG;

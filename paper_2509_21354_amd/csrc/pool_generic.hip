@@ -26,15 +26,19 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a)
 
     const T *Kp = static_cast<const T *>(a.K) + ((size_t)s * a.T_cap + (size_t)c * a.C) * D;
     const T *Vp = static_cast<const T *>(a.V) + ((size_t)s * a.T_cap + (size_t)c * a.C) * D;
+    const bool is_max = a.mode == KVEV_POOL_MAX;     // element-wise maximum instead of the mean
     float ak[EPL], av[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) ak[e] = av[e] = 0.f;
+    for (int e = 0; e < EPL; ++e) ak[e] = av[e] = is_max ? -INFINITY : 0.f;
     for (int j = grp; j < a.C; j += 16) {
         float x[EPL], y[EPL];
         VecLoad<T, EPL>::run(Kp + (size_t)j * D + cl * EPL, x);
         VecLoad<T, EPL>::run(Vp + (size_t)j * D + cl * EPL, y);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) { ak[e] += x[e]; av[e] += y[e]; }
+        for (int e = 0; e < EPL; ++e) {
+            ak[e] = is_max ? fmaxf(ak[e], x[e]) : ak[e] + x[e];
+            av[e] = is_max ? fmaxf(av[e], y[e]) : av[e] + y[e];
+        }
     }
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
@@ -44,16 +48,16 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a)
     __syncthreads();
     for (int i = tid; i < 2 * D; i += 256) {
         const int kv = i / D, e = i % D;
-        float sum = 0.f;
+        float sum = is_max ? -INFINITY : 0.f;
 #pragma unroll
-        for (int g = 0; g < 16; ++g) sum += red[(g * 2 + kv) * D + e];
-        mean[i] = sum / (float)a.C;
+        for (int g = 0; g < 16; ++g) sum = is_max ? fmaxf(sum, red[(g * 2 + kv) * D + e]) : sum + red[(g * 2 + kv) * D + e];
+        mean[i] = is_max ? sum : sum / (float)a.C;
     }
     __syncthreads();
 
     T *Kb = static_cast<T *>(a.Kbar) + ((size_t)s * a.N_cap + c) * D;
     T *Vb = static_cast<T *>(a.Vbar) + ((size_t)s * a.N_cap + c) * D;
-    if (a.mode == KVEV_POOL_MEAN) {
+    if (a.mode != KVEV_POOL_MLP) {
         for (int i = tid; i < 2 * D; i += 256) Storage<T>::store((i < D ? Kb : Vb) + (i % D), mean[i]);
         return;
     }

@@ -49,6 +49,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
     const int row0 = (blockIdx.x % tiles_per_layer) * 16;
 
     const bf16_t *K = static_cast<const bf16_t *>(a.K), *V = static_cast<const bf16_t *>(a.V);
+    const bool is_max = a.mode == KVEV_POOL_MAX;
 
     // ---- 1. stream the chunks, fp32 means to LDS ------------------------------
     for (int i = 0; i < 4; ++i) {
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
         const size_t tok0 = (s * a.T_cap + (size_t)c * a.C) * D + n * EPL;
         float sk[EPL], sv[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) sk[e] = sv[e] = 0.f;
+        for (int e = 0; e < EPL; ++e) sk[e] = sv[e] = is_max ? -INFINITY : 0.f;
         for (int j0 = 0; j0 < a.C; j0 += 32) {
             Raw<bf16_t, EPL> xk[8], xv[8];
             bool ok[8];
@@ -73,21 +74,32 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
             }
             // branch-free tail: a row past the chunk was loaded from the last row and gets weight 0
             // (x * 1 + s rounds as x + s), so every load of the group is in flight before the first use
+            // (the maximum needs no weight: the repeated last row changes nothing)
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const float wgt = ok[u] ? 1.f : 0.f;
                 float fk[EPL], fv[EPL];
                 xk[u].get(fk);
                 xv[u].get(fv);
+                if (is_max) {
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) { sk[e] = fmaf(fk[e], wgt, sk[e]); sv[e] = fmaf(fv[e], wgt, sv[e]); }
+                    for (int e = 0; e < EPL; ++e) { sk[e] = fmaxf(sk[e], fk[e]); sv[e] = fmaxf(sv[e], fv[e]); }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) { sk[e] = fmaf(fk[e], wgt, sk[e]); sv[e] = fmaf(fv[e], wgt, sv[e]); }
+                }
             }
         }
-        const float cf = (float)a.C;
+        const float cf = is_max ? 1.f : (float)a.C;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-            sk[e] += __shfl_xor(sk[e], 16); sk[e] += __shfl_xor(sk[e], 32);
-            sv[e] += __shfl_xor(sv[e], 16); sv[e] += __shfl_xor(sv[e], 32);
+            if (is_max) {
+                sk[e] = fmaxf(sk[e], __shfl_xor(sk[e], 16)); sk[e] = fmaxf(sk[e], __shfl_xor(sk[e], 32));
+                sv[e] = fmaxf(sv[e], __shfl_xor(sv[e], 16)); sv[e] = fmaxf(sv[e], __shfl_xor(sv[e], 32));
+            } else {
+                sk[e] += __shfl_xor(sk[e], 16); sk[e] += __shfl_xor(sk[e], 32);
+                sv[e] += __shfl_xor(sv[e], 16); sv[e] += __shfl_xor(sv[e], 32);
+            }
         }
         if (g4 == 0) {
 #pragma unroll
@@ -113,7 +125,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
     const size_t out_row = (((size_t)l * a.BH + r_c / nch) * a.N_cap + (a.c0 + r_c % nch)) * D;
     bf16_t *Kb = static_cast<bf16_t *>(a.Kbar), *Vb = static_cast<bf16_t *>(a.Vbar);
 
-    if (a.mode == KVEV_POOL_MEAN) {
+    if (a.mode != KVEV_POOL_MLP) {      // mean or maximum: the tile rows are the output (a bf16 maximum is its own hi term)
         for (int i = tid; i < 2 * 16 * (D / 2); i += 256) {
             const int kv = i / (16 * (D / 2)), rt = (i / (D / 2)) % 16, e = (i % (D / 2)) * 2;
             const int r = row0 + rt;

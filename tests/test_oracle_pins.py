@@ -116,6 +116,27 @@ def test_pool_closed_forms(oracle):
                           wV, 0, cfg.N)
 
 
+def test_pool_max_is_the_library_maximum(oracle):
+    """Mode MAX (the "pooling" alternative of section 3): the element-wise maximum of the
+    chunk's rows, an exact copy of one stored value, for both storage types."""
+    for cfg in (TINY, TINY.replace(dtype="bf16", number=92)):
+        t = _inputs(cfg)
+        Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MAX,
+                                       None, None, 0, cfg.N)
+        for got, src in ((Kbar, t["K"]), (Vbar, t["V"])):
+            want = src[..., :cfg.N * cfg.C, :].reshape(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d).amax(4)
+            if cfg.dtype == "bf16":
+                want = want.view(torch.int16).numpy().view(np.uint16)
+            else:
+                want = want.numpy()
+            assert (got == want).all()
+    # a chunk of one row is that row; a row repeated C times is that row
+    cfg = TINY
+    t = _inputs(cfg)
+    one = oracle.chunk_pool(t["K"], t["V"], cfg.T, 1, cfg.T, cfg.d_sum, oracle.POOL_MAX, None, None, 0, cfg.T)
+    assert (one[0] == t["K"].numpy()).all()
+
+
 def test_pool_bf16_storage_rounds_once(oracle):
     cfg = TINY.replace(dtype="bf16", number=91)
     t = _inputs(cfg)

@@ -162,7 +162,7 @@ POOL_CASES = [
 
 
 @pytest.mark.parametrize("cfg", POOL_CASES, ids=lambda c: c.name)
-@pytest.mark.parametrize("mode", [kb.POOL_MLP, kb.POOL_MEAN])
+@pytest.mark.parametrize("mode", [kb.POOL_MLP, kb.POOL_MEAN, kb.POOL_MAX], ids=["mlp", "mean", "max"])
 def test_chunk_pool(cfg, mode):
     t = synth.make_inputs(cfg, "cpu")
     g = dev(t)
@@ -183,7 +183,10 @@ def test_chunk_pool(cfg, mode):
     # rows outside [c0, c1) are not touched
     assert (Kbar[..., :c0, :] == 3.0).all() and (Kbar[..., c1:, :] == 3.0).all()
     assert (Vbar[..., :c0, :] == 3.0).all() and (Vbar[..., c1:, :] == 3.0).all()
-    if cfg.dtype == "bf16":
+    if mode == kb.POOL_MAX:      # a copy of one stored value: bit-exact
+        assert (orc.to_np(Kbar)[..., c0:c1, :] == rK[..., c0:c1, :]).all()
+        assert (orc.to_np(Vbar)[..., c0:c1, :] == rV[..., c0:c1, :]).all()
+    elif cfg.dtype == "bf16":
         frac, ulp = bf16_ulp_mismatch(Kbar[..., c0:c1, :], rK[..., c0:c1, :])
         # fp32-grade arithmetic: stored summaries equal the oracle's except for rare 1-ulp flips
         assert ulp <= 1 and frac < 5e-3, (frac, ulp)
@@ -288,6 +291,45 @@ def test_cold_step_end_to_end(number):
     ridx, rcnt = orc.select_topk(st.util.cpu(), cfg.T, cfg.C, cfg.W, cfg.k, st.k_cap)
     assert (orc.to_np(st.idx) == ridx).all() and (orc.to_np(st.count) == rcnt).all()
     assert (orc.to_np(st.count) == min(cfg.k, cfg.N_cand)).all()
+
+
+def test_threshold_step_end_to_end():
+    """The literal retention rule of section 3.2 through the whole step: the kept count is
+    ragged (0 .. N_cand per sequence), tau sits at the score quantile that keeps the paper's
+    average retention ratio (0.687, section 4.1).  Teacher-forced on the GPU's own gate scores
+    the kept set is bit-exact; attention over the ragged sets matches the oracle."""
+    cfg = synth.Config(160, "threshold_small", "bf16", L=2, B=2, H=3, d=128, T=1184, C=32, k=4, W=160,
+                       d_sum=64, d_g=64, Tq=1)
+    t = synth.make_inputs(cfg, "cpu")
+    g = dev(t)
+    n_cand = cfg.N_cand
+    st = kb.DecodeState(cfg, k_cap=n_cand)
+    sh, N = st.shape, cfg.N
+    kb.kvev_chunk_pool(sh, g["K"], g["V"], kb.POOL_MLP, kb.mlp_weights(g, "K"), kb.mlp_weights(g, "V"), 0, N,
+                       st.Kbar, st.Vbar, st.ws)
+    kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, kb.lstm_weights(g), 0, N, st.h, st.c, st.util, st.gate, st.ws)
+    torch.cuda.synchronize()
+    gate = st.gate.cpu().numpy()
+    tau = float(np.quantile(gate[..., :n_cand], 1.0 - 0.687))
+    kb.kvev_select(sh, None, st.gate, kb.SELECT_THRESHOLD, 0, tau, n_cand, st.idx, st.count)
+    O = torch.empty_like(g["Q"])
+    kb.kvev_gated_attention(sh, g["Q"], 1, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, n_cand, O, st.ws)
+    torch.cuda.synchronize()
+    ridx, rcnt = orc.select_threshold(gate, cfg.T, cfg.C, cfg.W, tau, n_cand)
+    cnt = orc.to_np(st.count)
+    assert (cnt == rcnt).all()
+    idx = orc.to_np(st.idx)
+    for s_ in np.ndindex(cnt.shape):
+        assert (idx[s_][:cnt[s_]] == ridx[s_][:cnt[s_]]).all()
+    kept = cnt.sum() / (cnt.size * n_cand)
+    assert abs(kept - 0.687) < 0.02 and cnt.min() < cnt.max()      # ragged, at the paper's ratio
+    ref = orc.gated_attention(t["Q"], t["K"], t["V"], st.Kbar.cpu(), st.Vbar.cpu(), st.idx.cpu(), st.count.cpu(),
+                              cfg.T, cfg.C, cfg.W)
+    assert_close_storage(O, ref, cfg.dtype, "O (threshold mode, teacher-forced)")
+    # and the oracle's own chain keeps about the same share at the same tau (scores agree to 1e-5)
+    r = orc.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    _, ocnt = orc.select_threshold(r["gate"], cfg.T, cfg.C, cfg.W, tau, n_cand)
+    assert abs(int(ocnt.sum()) - int(cnt.sum())) <= max(2, cnt.size // 2)
 
 
 def test_streaming_matches_oracle_and_cold_recompute():
