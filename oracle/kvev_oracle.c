@@ -443,6 +443,131 @@ int kvo_gated_attention(int dtype, int L, int B, int H, int d, int T, int T_cap,
     return rc;
 }
 
+/* ---------- physical eviction (sections 3.2-3.3, memory ratio of section 3.4) ----
+ * Chunks that are not kept are discarded, so what stays resident per sequence is
+ * a compact store of at most k summaries plus the raw window.  The store holds,
+ * ascending by chunk id: chunk_id [S,k_cap], util_c [S,k_cap], Kc, Vc [S,k_cap,d],
+ * count [S].  retain merges n_new freshly scored chunks (ids first_chunk ..
+ * first_chunk+n_new-1, all larger than every id in the store; summaries in rows
+ * 0..n_new-1 of Kbar_new/Vbar_new [S,n_new_cap,d], scores util_new [S,n_new_cap])
+ * and keeps the min(k, count+n_new) best under the order of kvo_select_topk
+ * (utility descending, NaN as minus infinity, ties to the lower id).  Because a
+ * chunk that drops out of the best k can never come back (scores of old chunks do
+ * not change), the store always equals the top-k over every chunk seen so far.
+ */
+typedef struct { float u; int id; int src; } keep_t;      /* src < 0: new row -src-1, else store slot */
+
+static int keep_cmp(const void *pa, const void *pb)
+{
+    const keep_t *a = pa, *b = pb;
+    if (a->u > b->u) return -1;
+    if (a->u < b->u) return 1;
+    return (a->id > b->id) - (a->id < b->id);
+}
+
+static int keep_id_cmp(const void *pa, const void *pb)
+{
+    const keep_t *a = pa, *b = pb;
+    return (a->id > b->id) - (a->id < b->id);
+}
+
+int kvo_retain(int dtype, int S, int d, int k, int k_cap, const void *Kbar_new, const void *Vbar_new,
+               const float *util_new, int n_new_cap, int first_chunk, int n_new,
+               void *Kc, void *Vc, int32_t *chunk_id, float *util_c, int32_t *count)
+{
+    if (S < 1 || d < 1 || k < 0 || k > k_cap || n_new < 0 || n_new > n_new_cap || first_chunk < 0)
+        return KVO_BAD_ARG;
+    size_t es = dtype == KVO_F32 ? 4 : 2, row = (size_t)d * es;
+    keep_t *all = malloc(sizeof(keep_t) * (size_t)(k_cap + n_new + 1));
+    unsigned char *tk = malloc(row * (size_t)(k_cap + 1)), *tv = malloc(row * (size_t)(k_cap + 1));
+    int rc = KVO_OK;
+    for (int s = 0; s < S && rc == KVO_OK; ++s) {
+        int m = count[s], n = 0;
+        if (m < 0 || m > k_cap) { rc = KVO_BAD_ARG; break; }
+        for (int j = 0; j < m; ++j) {
+            if (chunk_id[(size_t)s * k_cap + j] >= first_chunk) rc = KVO_BAD_ARG;
+            all[n].u = key_of(util_c[(size_t)s * k_cap + j]);
+            all[n].id = chunk_id[(size_t)s * k_cap + j];
+            all[n].src = j;
+            ++n;
+        }
+        for (int i = 0; i < n_new; ++i) {
+            all[n].u = key_of(util_new[(size_t)s * n_new_cap + i]);
+            all[n].id = first_chunk + i;
+            all[n].src = -i - 1;
+            ++n;
+        }
+        if (rc != KVO_OK) break;
+        int keep = k < n ? k : n;
+        qsort(all, (size_t)n, sizeof(keep_t), keep_cmp);
+        qsort(all, (size_t)keep, sizeof(keep_t), keep_id_cmp);
+        unsigned char *kc = (unsigned char *)Kc + (size_t)s * k_cap * row;
+        unsigned char *vc = (unsigned char *)Vc + (size_t)s * k_cap * row;
+        for (int j = 0; j < keep; ++j) {            /* gather into scratch first: slots move */
+            const unsigned char *sk, *sv;
+            if (all[j].src >= 0) {
+                sk = kc + (size_t)all[j].src * row;
+                sv = vc + (size_t)all[j].src * row;
+            } else {
+                size_t r = ((size_t)s * n_new_cap + (size_t)(-all[j].src - 1)) * row;
+                sk = (const unsigned char *)Kbar_new + r;
+                sv = (const unsigned char *)Vbar_new + r;
+            }
+            memcpy(tk + (size_t)j * row, sk, row);
+            memcpy(tv + (size_t)j * row, sv, row);
+        }
+        float *uc = util_c + (size_t)s * k_cap;
+        int32_t *ic = chunk_id + (size_t)s * k_cap;
+        float ut[4096];
+        if (keep > 4096) { rc = KVO_BAD_ARG; break; }
+        for (int j = 0; j < keep; ++j)              /* the stored score is the raw one (a NaN stays a NaN) */
+            ut[j] = all[j].src >= 0 ? uc[all[j].src] : util_new[(size_t)s * n_new_cap + (size_t)(-all[j].src - 1)];
+        memcpy(kc, tk, row * (size_t)keep);
+        memcpy(vc, tv, row * (size_t)keep);
+        for (int j = 0; j < keep; ++j) { uc[j] = ut[j]; ic[j] = all[j].id; }
+        count[s] = keep;
+    }
+    free(all);
+    free(tk);
+    free(tv);
+    return rc;
+}
+
+/* Eq. 1 over a compact store: rows 0..count-1 of Kc/Vc [S,k_cap,d] (the kept
+ * summaries, ascending chunk id) followed by rows 0..win_len-1 of the resident
+ * raw window Kw/Vw [S,W_cap,d].  Same arithmetic as kvo_gated_attention. */
+int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, int W_cap, const void *Q,
+                          int Tq, const void *Kw, const void *Vw, const void *Kc, const void *Vc,
+                          const int32_t *count, int k_cap, void *O)
+{
+    if (L < 1 || B < 1 || H < 1 || d < 1 || win_len < 0 || win_len > W_cap || Tq < 0 || k_cap < 0)
+        return KVO_BAD_ARG;
+    int n_max = k_cap + win_len;
+    const void **kb = malloc(sizeof(void *) * (size_t)(n_max + 1));
+    const void **vb = malloc(sizeof(void *) * (size_t)(n_max + 1));
+    size_t *off = malloc(sizeof(size_t) * (size_t)(n_max + 1));
+    double *logit = malloc(sizeof(double) * (size_t)(n_max + 1));
+    double *acc = malloc(sizeof(double) * (size_t)d);
+    int rc = KVO_OK;
+    size_t S = (size_t)L * B * H;
+    for (size_t s = 0; s < S; ++s) {
+        int m = count[s], n = 0;
+        if (m < 0 || m > k_cap) { rc = KVO_BAD_ARG; break; }
+        for (int j = 0; j < m; ++j) { kb[n] = Kc; vb[n] = Vc; off[n] = (s * k_cap + (size_t)j) * d; ++n; }
+        for (int t = 0; t < win_len; ++t) { kb[n] = Kw; vb[n] = Vw; off[n] = (s * W_cap + (size_t)t) * d; ++n; }
+        for (int i = 0; i < Tq; ++i) {
+            size_t qo = (s * Tq + i) * d;
+            attend_rows(dtype, d, Q, qo, kb, vb, off, n, O, qo, logit, acc, NULL);
+        }
+    }
+    free(kb);
+    free(vb);
+    free(off);
+    free(logit);
+    free(acc);
+    return rc;
+}
+
 /* Dense baseline: Eq. 1 over raw tokens 0 .. T-1 of the full cache. */
 int kvo_dense_attention(int dtype, int L, int B, int H, int d, int T, int T_cap, const void *Q,
                         int Tq, const void *K, const void *V, void *O, double *probs,

@@ -181,6 +181,32 @@ def gated_attention(Q, K, V, Kbar, Vbar, idx, count, T, C, W, want_probs=False):
     return (O, probs) if want_probs else O
 
 
+def retain(Kbar_new, Vbar_new, util_new, first_chunk, n_new, k, Kc, Vc, chunk_id, util_c, count):
+    """Physical eviction (sections 3.2-3.3): merge n_new freshly scored chunks into the compact
+    store (Kc, Vc [...,k_cap,d], chunk_id, util_c [...,k_cap], count [...]), in place."""
+    Kn, Vn = to_np(Kbar_new), to_np(Vbar_new)
+    un = np.ascontiguousarray(to_np(util_new), dtype=np.float32)
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous and chunk_id.dtype == np.int32
+    assert util_c.dtype == np.float32 and count.dtype == np.int32
+    lead, k_cap, d = Kc.shape[:-2], Kc.shape[-2], Kc.shape[-1]
+    S = int(np.prod(lead)) if lead else 1
+    rc = lib().kvo_retain(dtype_code(Kc), S, d, k, k_cap, _p(Kn), _p(Vn), _p(un), Kn.shape[-2], first_chunk,
+                          n_new, _p(Kc), _p(Vc), _p(chunk_id), _p(util_c), _p(count))
+    _check(rc, "retain")
+
+
+def compact_attention(Q, Kw, Vw, win_len, Kc, Vc, count):
+    """Eq. 1 over kept summaries (compact store) + resident raw window."""
+    Q, Kw, Vw, Kc, Vc = (to_np(x) for x in (Q, Kw, Vw, Kc, Vc))
+    count = np.ascontiguousarray(to_np(count), dtype=np.int32)
+    L, B, H, Tq, d = Q.shape
+    O = np.zeros_like(Q)
+    rc = lib().kvo_compact_attention(dtype_code(Q), L, B, H, d, win_len, Kw.shape[3], _p(Q), Tq, _p(Kw), _p(Vw),
+                                     _p(Kc), _p(Vc), _p(count), Kc.shape[3], _p(O))
+    _check(rc, "compact_attention")
+    return O
+
+
 def dense_attention(Q, K, V, T, want_probs=False):
     """Eq. 1 over the whole cache."""
     Q, K, V = (to_np(x) for x in (Q, K, V))

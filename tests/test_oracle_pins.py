@@ -429,6 +429,81 @@ def test_streaming_equals_cold_recompute_at_every_step(oracle):
         assert st["count"].max() == min(cfg.k, max(0, T - cfg.W) // cfg.C)
 
 
+def _store(lead, k_cap, d, np_dtype):
+    return (np.zeros(lead + (k_cap, d), np_dtype), np.zeros(lead + (k_cap, d), np_dtype),
+            np.full(lead + (k_cap,), -1, np.int32), np.zeros(lead + (k_cap,), np.float32), np.zeros(lead, np.int32))
+
+
+def test_retain_stream_equals_cold_topk_and_brute_force(oracle):
+    """Physical eviction: feeding the scored chunks frame by frame into the compact store leaves
+    exactly the top-k over everything seen (same order rule as select: utility descending, NaN as
+    minus infinity, ties to the lower id), ascending, with the rows and scores of those chunks."""
+    rng = np.random.default_rng(77)
+    lead, d, k, k_cap, N = (2, 3), 8, 5, 7, 40
+    for dtype in (np.float32, np.uint16):
+        util = rng.standard_normal(lead + (N,)).astype(np.float32)
+        util[0, 0, 5] = util[0, 0, 9] = util[0, 0, 30] = 0.25          # ties
+        util[1, 1, 3] = np.nan
+        util[1, 2, :] = 1.0                                             # all equal: lowest ids win
+        Kbar = rng.integers(0, 60000, lead + (N, d)).astype(dtype)
+        Vbar = rng.integers(0, 60000, lead + (N, d)).astype(dtype)
+        Kc, Vc, ids, uc, cnt = _store(lead, k_cap, d, dtype)
+        seen = 0
+        for n_new in (3, 0, 1, 8, 6, 2, 20):
+            Kn = np.ascontiguousarray(Kbar[..., seen:seen + n_new + 2, :])     # staging with spare rows
+            Vn = np.ascontiguousarray(Vbar[..., seen:seen + n_new + 2, :])
+            un = np.ascontiguousarray(util[..., seen:seen + n_new + 2])
+            if Kn.shape[-2] == 0:
+                Kn, Vn, un = np.zeros(lead + (1, d), dtype), np.zeros(lead + (1, d), dtype), np.zeros(lead + (1,), np.float32)
+            oracle.retain(Kn, Vn, un, seen, n_new, k, Kc, Vc, ids, uc, cnt)
+            seen += n_new
+            # cold: top-k over the chunks seen so far (window of 0 tokens, chunk size 1: every chunk a candidate)
+            idx, c = oracle.select_topk(util[..., :max(seen, 1)], seen, 1, 0, k, k_cap)
+            assert (cnt == c).all()
+            for s_ in np.ndindex(lead):
+                m = cnt[s_]
+                assert (ids[s_][:m] == idx[s_][:m]).all()
+                assert (Kc[s_][:m] == Kbar[s_][idx[s_][:m]]).all() and (Vc[s_][:m] == Vbar[s_][idx[s_][:m]]).all()
+                assert np.array_equal(uc[s_][:m], util[s_][idx[s_][:m]], equal_nan=True)
+                # brute force in plain Python
+                key = lambda c_: (-(util[s_][c_] if not np.isnan(util[s_][c_]) else -np.inf), c_)
+                want = sorted(sorted(range(seen), key=key)[:k])
+                assert list(ids[s_][:m]) == want
+        assert seen == N
+    # k = 0 keeps nothing; ids that do not grow are refused
+    Kc, Vc, ids, uc, cnt = _store(lead, k_cap, d, np.float32)
+    Kn = rng.standard_normal(lead + (4, d)).astype(np.float32)
+    un = rng.standard_normal(lead + (4,)).astype(np.float32)
+    oracle.retain(Kn, Kn, un, 0, 4, 0, Kc, Vc, ids, uc, cnt)
+    assert (cnt == 0).all()
+    oracle.retain(Kn, Kn, un, 0, 4, 3, Kc, Vc, ids, uc, cnt)
+    with pytest.raises(ValueError):
+        oracle.retain(Kn, Kn, un, 2, 4, 3, Kc, Vc, ids, uc, cnt)
+
+
+def test_compact_attention_equals_gated_attention_on_the_gathered_rows(oracle):
+    """After eviction only kept summaries and the raw window are resident; attending them gives the
+    very same output as attending the full caches through idx (same rows, same order)."""
+    for cfg in (TINY, TINY.replace(dtype="bf16", number=93)):
+        t = _inputs(cfg)
+        r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+        n_cand = cfg.N_cand
+        win0 = n_cand * cfg.C
+        K, V = oracle.to_np(t["K"]), oracle.to_np(t["V"])
+        Kw = np.ascontiguousarray(K[..., win0:cfg.T, :])
+        Vw = np.ascontiguousarray(V[..., win0:cfg.T, :])
+        Kc = np.zeros(K.shape[:3] + (cfg.k + 1, cfg.d), K.dtype)
+        Vc = np.zeros_like(Kc)
+        for s_ in np.ndindex(K.shape[:3]):
+            m = r["count"][s_]
+            Kc[s_][:m] = r["Kbar"][s_][r["idx"][s_][:m]]
+            Vc[s_][:m] = r["Vbar"][s_][r["idx"][s_][:m]]
+        O = oracle.compact_attention(t["Q"], Kw, Vw, cfg.T - win0, Kc, Vc, r["count"])
+        assert (O == r["O"]).all()
+        # resident rows: k + window instead of T (the memory ratio of section 3.4)
+        assert Kc.shape[3] - 1 + Kw.shape[3] == cfg.k + cfg.T - win0 < cfg.T
+
+
 def test_edge_cases(oracle):
     cfg = TINY
     t = _inputs(cfg)
