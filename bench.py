@@ -296,6 +296,52 @@ def main():
                 out["threshold_mode"]["speedup_vs_dense"] = round(out["dense"]["us_per_step"] / t_thr, 2)
             del idx_t, cnt_t, ws_t
 
+    # ---- physical eviction (sections 3.2-3.4): compact store + resident window instead of the whole cache ----
+    if not args.only and cfg.N_cand > 0:
+        for n, f in stages[:3]:
+            f(sets[0])
+        lead = (cfg.L, cfg.B, cfg.H)
+        n_cand, win0 = cfg.N_cand, cfg.N_cand * cfg.C
+        kc = st.k_cap
+        Kc = torch.zeros(lead + (kc, cfg.d), dtype=cfg.torch_dtype, device=dev); Vc = torch.zeros_like(Kc)
+        ids = torch.full(lead + (kc,), -1, dtype=torch.int32, device=dev)
+        ucs = torch.zeros(lead + (kc,), dtype=torch.float32, device=dev)
+        cn = torch.zeros(lead, dtype=torch.int32, device=dev)
+        if kc + n_cand <= 4000:
+            def retain_all(t):
+                cn.zero_()
+                kb.kvev_retain(sh, cfg.k, kc, st.Kbar, st.Vbar, st.util, st.N_cap, 0, n_cand, Kc, Vc, ids, ucs, cn)
+            frame_chunks = max(1, min(n_cand, 256 // cfg.C))
+
+            def retain_frame(t):            # one frame's worth of chunks leaving the window
+                kb.kvev_retain(sh, cfg.k, kc, st.Kbar, st.Vbar, st.util, st.N_cap, n_cand, frame_chunks, Kc, Vc, ids, ucs, cn)
+            t_all = time_alone(retain_all, 30)
+            retain_all(None)
+            t_frame = time_alone(retain_frame, 30)
+            retain_all(None)
+            wlen = cfg.T - win0
+            Kw = [t_["K"][..., win0:cfg.T, :].contiguous() for t_ in sets]
+            Vw = [t_["V"][..., win0:cfg.T, :].contiguous() for t_ in sets]
+            shw = kb.make_shape(cfg, T=wlen, T_cap=wlen, N_cap=kc)
+            wsw = kb.alloc_workspace(kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, shw, Tq, kc), dev)
+            it = [0]
+
+            def compact_attend(t):
+                i = it[0] % R; it[0] += 1
+                kb.kvev_compact_attention(shw, sets[i]["Q"], Tq, Kw[i], Vw[i], Kc, Vc, cn, kc, O, wsw)
+            t_ca = time_alone(compact_attend, max(50, args.steps))
+            rows = min(cfg.k, n_cand) + wlen
+            out["eviction"] = {"resident_rows_per_sequence": rows, "cached_tokens": cfg.T,
+                               "memory_ratio_n_over_W_plus_M": round(cfg.T / rows, 2),
+                               "paper_memory_reduction": 1.87,
+                               "resident_kv_bytes": 2 * S * rows * cfg.d * cfg.elem_size,
+                               "full_kv_bytes": 2 * S * cfg.T * cfg.d * cfg.elem_size,
+                               "retain_all_candidates_us": round(t_all, 3),
+                               "retain_one_frame_us": round(t_frame, 3),
+                               "compact_attention_us": round(t_ca, 3)}
+            del Kw, Vw, wsw
+        del Kc, Vc, ids, ucs, cn
+
     # ---- the paper's closed-form estimate (Eq. 4-7) at this configuration, beside what was measured ----
     if not args.only:
         from paper_2509_21354_amd import cost_model as cm

@@ -42,7 +42,7 @@ enum { KVEV_F32 = 0, KVEV_BF16 = 1 };           /* storage type of Q/K/V, summar
 enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1, KVEV_POOL_MAX = 2 };
 enum { KVEV_SELECT_TOPK = 0, KVEV_SELECT_THRESHOLD = 1 };
 enum { KVEV_OP_CHUNK_POOL = 0, KVEV_OP_LSTM_GATE = 1, KVEV_OP_SELECT = 2,
-       KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4 };
+       KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4, KVEV_OP_COMPACT_ATTENTION = 5 };
 
 /* Problem shape.  L layers are batched in one call; a "sequence" is one
  * (layer, batch row, head) triple, S = L*B*H of them, each independent.
@@ -142,9 +142,42 @@ int kvev_dense_attention(const kvev_shape *shape, const void *Q, int Tq, const v
                          const void *V, int causal, void *O, void *ws, size_t ws_bytes,
                          void *stream);
 
+/* Physical eviction (sections 3.2-3.3: a chunk that is not kept is discarded;
+ * section 3.4: the cache shrinks by n / (W + M)).  Per sequence a compact store
+ * holds at most k kept summaries, ascending by chunk id:
+ *   Kc, Vc    [L,B,H,k_cap,d]  storage dtype     chunk_id [L,B,H,k_cap] int32
+ *   util_c    [L,B,H,k_cap]    fp32 scores        count    [L,B,H] int32 (in/out;
+ *                                                  zero it before the first call)
+ * This call merges n_new freshly scored chunks, ids first_chunk .. first_chunk +
+ * n_new - 1 (summaries in rows 0 .. n_new-1 of Kbar_new, Vbar_new
+ * [L,B,H,n_new_cap,d], utilities util_new [L,B,H,n_new_cap]) and keeps the
+ * min(k, count + n_new) best under the order of KVEV_SELECT_TOPK (utility
+ * descending, NaN as minus infinity, ties to the lower id), in place.  Because
+ * the score of an old chunk never changes, the store always equals the top-k
+ * over every chunk merged so far, and everything else (the chunk's raw tokens
+ * once it left the window, its summary) can be freed by the caller.  Rows and
+ * integers are copied exactly.  first_chunk must exceed every id in the store
+ * (ids arrive in temporal order; device data, not checked).  Only L, B, H, d and
+ * dtype of `shape` are used.  Needs 0 <= k <= k_cap, 0 <= n_new <= n_new_cap,
+ * k_cap + n_new <= 4000.  No workspace. */
+int kvev_retain(const kvev_shape *shape, int k, int k_cap, const void *Kbar_new, const void *Vbar_new,
+                const float *util_new, int n_new_cap, int first_chunk, int n_new, void *Kc, void *Vc,
+                int32_t *chunk_id, float *util_c, int32_t *count, void *stream);
+
+/* Eq. 1 over what is resident after eviction: rows 0 .. count-1 of the compact
+ * store Kc / Vc followed by the raw window.  Here `shape` describes the resident
+ * raw buffer: Kw, Vw are [L,B,H,T_cap,d] and hold the window's tokens in rows
+ * 0 .. T-1 (C, W, N_cap of the shape are not used).  Same arithmetic, row order
+ * and rounding as kvev_gated_attention over the same rows, so the two give the
+ * same bits.  Workspace: kvev_workspace_bytes(KVEV_OP_COMPACT_ATTENTION, shape,
+ * Tq, k_cap). */
+int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const void *Kw, const void *Vw,
+                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, void *O,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape.  `n` is Tq
  * for the attention ops and chunk_end - chunk_begin for pool / gate; k_cap is
- * used by KVEV_OP_GATED_ATTENTION only.  Returns 0 when none is needed or the
+ * used by KVEV_OP_GATED_ATTENTION and KVEV_OP_COMPACT_ATTENTION only.  Returns 0 when none is needed or the
  * arguments are invalid. */
 size_t kvev_workspace_bytes(int op, const kvev_shape *shape, int n, int k_cap);
 

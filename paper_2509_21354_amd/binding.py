@@ -22,11 +22,11 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 F32, BF16 = 0, 1
 POOL_MEAN, POOL_MLP, POOL_MAX = 0, 1, 2
 SELECT_TOPK, SELECT_THRESHOLD = 0, 1
-OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION = range(5)
+OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, OP_COMPACT_ATTENTION = range(6)
 
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
-           "kvev_dense_attention", "kvev_workspace_bytes", "kvev_status_string",
-           "kvev_last_hip_error", "kvev_version")
+           "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
+           "kvev_status_string", "kvev_last_hip_error", "kvev_version")
 
 
 class Shape(ctypes.Structure):
@@ -68,13 +68,15 @@ def lib() -> ctypes.CDLL:
         L.kvev_select.argtypes = [shp, vp, vp, ci, ci, ctypes.c_float, ci, vp, vp, vp]
         L.kvev_gated_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_dense_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, sz, vp]
+        L.kvev_retain.argtypes = [shp, ci, ci, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, ci, vp, vp, sz, vp]
         L.kvev_workspace_bytes.argtypes = [ci, shp, ci, ci]
         L.kvev_workspace_bytes.restype = sz
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
         for n in ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
-                  "kvev_dense_attention", "kvev_version"):
+                  "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_version"):
             getattr(L, n).restype = ci
         _lib = L
     return _lib
@@ -155,6 +157,21 @@ def kvev_dense_attention(shape: Shape, Q, Tq, K, V, O, ws=None, causal=0):
     st = lib().kvev_dense_attention(ctypes.byref(shape), _ptr(Q), Tq, _ptr(K), _ptr(V), causal, _ptr(O),
                                     _ptr(ws), ws.numel() if ws is not None else 0, _stream())
     _check(st, "kvev_dense_attention")
+
+
+def kvev_retain(shape: Shape, k, k_cap, Kbar_new, Vbar_new, util_new, n_new_cap, first_chunk, n_new, Kc, Vc,
+                chunk_id, util_c, count):
+    st = lib().kvev_retain(ctypes.byref(shape), k, k_cap, _ptr(Kbar_new), _ptr(Vbar_new), _ptr(util_new),
+                           n_new_cap, first_chunk, n_new, _ptr(Kc), _ptr(Vc), _ptr(chunk_id), _ptr(util_c),
+                           _ptr(count), _stream())
+    _check(st, "kvev_retain")
+
+
+def kvev_compact_attention(shape: Shape, Q, Tq, Kw, Vw, Kc, Vc, count, k_cap, O, ws=None):
+    st = lib().kvev_compact_attention(ctypes.byref(shape), _ptr(Q), Tq, _ptr(Kw), _ptr(Vw), _ptr(Kc), _ptr(Vc),
+                                      _ptr(count), k_cap, _ptr(O), _ptr(ws),
+                                      ws.numel() if ws is not None else 0, _stream())
+    _check(st, "kvev_compact_attention")
 
 
 class DecodeState:

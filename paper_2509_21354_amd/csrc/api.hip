@@ -21,13 +21,13 @@ static int hip_fail(hipError_t e)
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // 0 when the shape itself is usable, else a status.
-static int check_shape(const kvev_shape *sh)
+static int check_shape(const kvev_shape *sh, bool chunked = true)
 {
     if (!sh) return KVEV_ERR_INVALID_ARG;
     if (sh->L < 1 || sh->B < 1 || sh->H < 1 || sh->d < 1 || sh->C < 1 || sh->T < 0 || sh->T_cap < 1 ||
         sh->N_cap < 0 || sh->W < 0 || sh->d_sum < 1 || sh->d_g < 1)
         return KVEV_ERR_INVALID_ARG;
-    if (sh->T > sh->T_cap || sh->T / sh->C > sh->N_cap) return KVEV_ERR_INVALID_ARG;
+    if (sh->T > sh->T_cap || (chunked && sh->T / sh->C > sh->N_cap)) return KVEV_ERR_INVALID_ARG;
     if ((int64_t)sh->L * sh->B * sh->H > (int64_t)1 << 24) return KVEV_ERR_INVALID_ARG;
     if (sh->dtype != KVEV_F32 && sh->dtype != KVEV_BF16) return KVEV_ERR_UNSUPPORTED;
     if (sh->d != 64 && sh->d != 128) return KVEV_ERR_UNSUPPORTED;
@@ -76,20 +76,22 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
                             int k_cap, int gated, int causal, void *O, void *ws, size_t ws_bytes,
                             void *stream)
 {
-    int rc = check_shape(sh);
+    int rc = check_shape(sh, gated != 2);     // a compact store has no chunk grid over the raw buffer
     if (rc) return rc;
     if (!Q || !K || !V || !O || Tq < 0 || !aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
         return KVEV_ERR_INVALID_ARG;
-    if (gated && (!Kbar || !Vbar || !idx || !count || k_cap < 0 || !aligned16(Kbar) || !aligned16(Vbar)))
+    // gated == 2: compact store (no index list, N_cap = k_cap rows per sequence, raw rows 0 .. T-1)
+    const bool compact = gated == 2;
+    if (gated && (!Kbar || !Vbar || (!idx && !compact) || !count || k_cap < 0 || !aligned16(Kbar) || !aligned16(Vbar)))
         return KVEV_ERR_INVALID_ARG;
-    if (gated && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
+    if (gated && !compact && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
     if (causal != 0) return KVEV_ERR_UNSUPPORTED;
     if (Tq == 0) return KVEV_OK;
     if ((int64_t)sh->L * sh->B * sh->H * Tq > (int64_t)1 << 26) return KVEV_ERR_INVALID_ARG;
 
     const int ncand = n_cand_of(sh);
-    const int win0 = gated ? ncand * sh->C : 0;
-    const int kmax = gated ? (k_cap < ncand ? k_cap : ncand) : 0;
+    const int win0 = gated == 1 ? ncand * sh->C : 0;
+    const int kmax = compact ? k_cap : gated ? (k_cap < ncand ? k_cap : ncand) : 0;
     const int n_rows = kmax + sh->T - win0;
     // a frame of queries on bf16 storage goes to the matrix-core kernel (no split, no scratch)
     const bool mq = attn_takes_mq(sh, Tq);
@@ -100,8 +102,8 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     a.Q = Q; a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar; a.idx = idx; a.count = count; a.O = O;
     a.part = p.nsplit > 1 ? static_cast<float *>(ws) : nullptr;
     a.S = sh->L * sh->B * sh->H; a.Tq = Tq; a.d = sh->d;
-    a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = sh->N_cap; a.k_cap = k_cap;
-    a.win0 = win0; a.gated = gated;
+    a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = compact ? k_cap : sh->N_cap; a.k_cap = k_cap;
+    a.win0 = win0; a.gated = gated ? 1 : 0;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
     hipError_t e = mq ? launch_attn_mq(a, static_cast<hipStream_t>(stream))
@@ -253,9 +255,37 @@ int kvev_dense_attention(const kvev_shape *sh, const void *Q, int Tq, const void
                             stream);
 }
 
+int kvev_compact_attention(const kvev_shape *sh, const void *Q, int Tq, const void *Kw, const void *Vw,
+                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, void *O, void *ws,
+                           size_t ws_bytes, void *stream)
+{
+    return attention_common(sh, Q, Tq, Kw, Vw, Kc, Vc, nullptr, count, k_cap, 2, 0, O, ws, ws_bytes, stream);
+}
+
+int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, const void *Vbar_new,
+                const float *util_new, int n_new_cap, int first_chunk, int n_new, void *Kc, void *Vc,
+                int32_t *chunk_id, float *util_c, int32_t *count, void *stream)
+{
+    int rc = check_shape(sh, false);
+    if (rc) return rc;
+    if (k < 0 || k > k_cap || n_new < 0 || n_new > n_new_cap || first_chunk < 0) return KVEV_ERR_INVALID_ARG;
+    if ((int64_t)k_cap + n_new > 4000) return KVEV_ERR_INVALID_ARG;
+    if (!Kc || !Vc || !chunk_id || !util_c || !count || !aligned16(Kc) || !aligned16(Vc)) return KVEV_ERR_INVALID_ARG;
+    if (n_new > 0 && (!Kbar_new || !Vbar_new || !util_new || !aligned16(Kbar_new) || !aligned16(Vbar_new)))
+        return KVEV_ERR_INVALID_ARG;
+    RetainArgs a;
+    a.Kn = Kbar_new; a.Vn = Vbar_new; a.un = util_new; a.Kc = Kc; a.Vc = Vc; a.ids = chunk_id; a.uc = util_c;
+    a.count = count;
+    a.S = sh->L * sh->B * sh->H;
+    a.row_bytes = sh->d * (sh->dtype == KVEV_F32 ? 4 : 2);
+    a.k = k; a.k_cap = k_cap; a.n_new_cap = n_new_cap; a.first_chunk = first_chunk; a.n_new = n_new;
+    hipError_t e = launch_retain(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
 size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
 {
-    if (check_shape(sh) != KVEV_OK || n < 0) return 0;
+    if (check_shape(sh, op != KVEV_OP_COMPACT_ATTENTION) != KVEV_OK || n < 0) return 0;
     switch (op) {
     case KVEV_OP_LSTM_GATE: {
         const size_t per = lstm_ws_per_step(sh);
@@ -270,6 +300,9 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
     }
     case KVEV_OP_DENSE_ATTENTION:
         return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, sh->T).ws_bytes;
+    case KVEV_OP_COMPACT_ATTENTION:
+        if (k_cap < 0) return 0;
+        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, k_cap + sh->T).ws_bytes;
     default:
         return 0;
     }

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
 
     const size_t seq_raw = (size_t)s * a.T_cap;
     const size_t seq_sum = (size_t)s * a.N_cap;
-    const int32_t *idx = a.idx + (size_t)s * a.k_cap;
+    const int32_t *idx = a.idx ? a.idx + (size_t)s * a.k_cap : nullptr;   // null: the store is compact, row j is entry j
 
     for (int base = j0; base < j1; base += 16 * U) {
         Raw<T, EPL> kr[U], vr[U];
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
             size_t off;
             const T *kb, *vb;
             if (j < cnt) {
-                int c = min(max(idx[j], 0), a.N_cap - 1);
+                int c = min(max(idx ? idx[j] : j, 0), a.N_cap - 1);
                 off = (seq_sum + c) * D;
                 kb = Kbar; vb = Vbar;
             } else {

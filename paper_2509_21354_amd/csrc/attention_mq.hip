@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
     int cnt = 0;
     if (a.gated) cnt = min(max(a.count[s], 0), a.k_cap);
     const int nrows = cnt + (a.T - a.win0);
-    const int32_t *idx = a.idx + (size_t)s * a.k_cap;
+    const int32_t *idx = a.idx ? a.idx + (size_t)s * a.k_cap : nullptr;   // null: compact store, row j is entry j
     const size_t seq_raw = (size_t)s * a.T_cap, seq_sum = (size_t)s * a.N_cap;
 
     // staging role of this thread: column chunk dc of rows sr, sr + 256/(D/8), ...
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
     {                                                                                                  \
         const int j = min((J0) + sr + RSTEP * i, nrows - 1);                                           \
         const bool sm = j < cnt;                                                                       \
-        const int c_ = sm ? min(max(idx[j], 0), a.N_cap - 1) : 0;                                      \
+        const int c_ = sm ? min(max(idx ? idx[j] : j, 0), a.N_cap - 1) : 0;                            \
         const size_t off = (sm ? (seq_sum + c_) : (seq_raw + a.win0 + (j - cnt))) * D + dc * 8;        \
         kreg[i] = *reinterpret_cast<const u32x4_t *>((sm ? Kbar : K) + off);                             \
         vreg[i] = *reinterpret_cast<const u32x4_t *>((sm ? Vbar : V) + off);                             \

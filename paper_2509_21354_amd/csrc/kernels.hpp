@@ -48,9 +48,20 @@ struct SelectArgs {
     float tau;
 };
 
+struct RetainArgs {
+    const void *Kn, *Vn;          // new summaries [S, n_new_cap, d]
+    const float *un;              // their scores [S, n_new_cap]
+    void *Kc, *Vc;                // compact store [S, k_cap, d]
+    int32_t *ids;                 // chunk ids of the store rows [S, k_cap], ascending
+    float *uc;                    // their scores [S, k_cap]
+    int32_t *count;               // [S]
+    int S, row_bytes, k, k_cap, n_new_cap, first_chunk, n_new;
+};
+
 hipError_t launch_attn_decode(const AttnArgs &a, int dtype, hipStream_t st);
 hipError_t launch_attn_mq(const AttnArgs &a, hipStream_t st);           // bf16 MFMA, many queries
 hipError_t launch_select(const SelectArgs &a, hipStream_t st);
+hipError_t launch_retain(const RetainArgs &a, hipStream_t st);
 hipError_t launch_pool_generic(const PoolArgs &a, int dtype, hipStream_t st);
 hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st);          // bf16
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);

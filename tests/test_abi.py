@@ -108,3 +108,24 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(kb, "LIB_PATH", str(tmp_path / "libkvev.so"))
     with pytest.raises(FileNotFoundError):
         kb.lib()
+
+
+def test_retain_and_compact_attention_validation():
+    L = kb.lib()
+    sh = _shape()
+    r = ctypes.byref(sh)
+    ok = (FAKE, FAKE, FAKE, 8, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    assert L.kvev_retain(r, 33, 32, *ok) == kb.ERR_INVALID_ARG               # k > k_cap
+    assert L.kvev_retain(r, -1, 32, *ok) == kb.ERR_INVALID_ARG
+    assert L.kvev_retain(r, 4, 32, FAKE, FAKE, FAKE, 8, 0, 9, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG   # n_new > cap
+    assert L.kvev_retain(r, 4, 3990, FAKE, FAKE, FAKE, 16, 0, 16, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_retain(r, 4, 32, None, FAKE, FAKE, 8, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_retain(r, 4, 32, FAKE, FAKE, FAKE, 8, 0, 4, None, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_retain(r, 4, 32, FAKE, FAKE, FAKE, 8, -1, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, None, FAKE, FAKE, 32, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, None, 32, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, -1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    big = _shape()                                                            # T = 4096 raw rows: split, needs scratch
+    assert kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, big, 1, 32) > 0
+    assert L.kvev_compact_attention(ctypes.byref(big), FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 32, FAKE, None, 0, None) == kb.ERR_WORKSPACE
+
