@@ -568,6 +568,67 @@ int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, in
     return rc;
 }
 
+/* Grouped-query heads and causal frames (section 4.1 names grouped-query
+ * attention with fewer key-value heads than query heads; section 3.2 states
+ * strict causality).  Readings: query head h reads the cache, summaries and kept
+ * set of key-value head h / (H / H_kv); with causal != 0 the Tq queries ARE the
+ * last Tq cached tokens, query i sitting at position T - Tq + i, and it sees the
+ * kept summaries (all older than the window) and raw tokens up to and including
+ * its own position only.  gated == 0: the dense baseline over tokens 0 .. (own
+ * position or T-1).
+ *   Q, O [L,B,H,Tq,d];  K, V [L,B,H_kv,T_cap,d];  Kbar, Vbar [L,B,H_kv,N_cap,d];
+ *   idx [L,B,H_kv,k_cap];  count [L,B,H_kv]
+ * Needs H % H_kv == 0 and, when causal, Tq <= number of raw rows attended. */
+int kvo_attention_ext(int dtype, int L, int B, int H, int H_kv, int d, int T, int T_cap, int C, int N_cap,
+                      int W, int gated, int causal, const void *Q, int Tq, const void *K, const void *V,
+                      const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
+                      int k_cap, void *O)
+{
+    if (L < 1 || B < 1 || H < 1 || H_kv < 1 || H % H_kv != 0 || d < 1 || C < 1 || T < 0 || T > T_cap ||
+        W < 0 || Tq < 0 || k_cap < 0)
+        return KVO_BAD_ARG;
+    int n_cand = gated ? (T > W ? T - W : 0) / C : 0;
+    int win0 = n_cand * C;
+    if (causal && Tq > T - win0)
+        return KVO_BAD_ARG;
+    int n_max = (gated ? k_cap : 0) + (T - win0);
+    const void **kb = malloc(sizeof(void *) * (size_t)(n_max + 1));
+    const void **vb = malloc(sizeof(void *) * (size_t)(n_max + 1));
+    size_t *off = malloc(sizeof(size_t) * (size_t)(n_max + 1));
+    double *logit = malloc(sizeof(double) * (size_t)(n_max + 1));
+    double *acc = malloc(sizeof(double) * (size_t)d);
+    int rc = KVO_OK, G = H / H_kv;
+    for (int l = 0; l < L && rc == KVO_OK; ++l)
+        for (int b = 0; b < B && rc == KVO_OK; ++b)
+            for (int h = 0; h < H && rc == KVO_OK; ++h) {
+                size_t sq = ((size_t)l * B + b) * H + h;
+                size_t sk = ((size_t)l * B + b) * H_kv + (size_t)(h / G);
+                int n = 0;
+                if (gated) {
+                    int m = count[sk];
+                    if (m < 0 || m > k_cap) { rc = KVO_BAD_ARG; break; }
+                    for (int i = 0; i < m; ++i) {
+                        int c = idx[sk * k_cap + i];
+                        if (c < 0 || c >= n_cand || c >= N_cap) { rc = KVO_BAD_ARG; break; }
+                        kb[n] = Kbar; vb[n] = Vbar; off[n] = (sk * N_cap + (size_t)c) * d; ++n;
+                    }
+                    if (rc != KVO_OK) break;
+                }
+                for (int t = win0; t < T; ++t) { kb[n] = K; vb[n] = V; off[n] = (sk * T_cap + (size_t)t) * d; ++n; }
+                for (int i = 0; i < Tq; ++i) {
+                    size_t qo = (sq * Tq + i) * d;
+                    int n_i = causal ? n - (Tq - 1 - i) : n;     /* rows after the query's own token are hidden */
+                    attend_rows(dtype, d, Q, qo, kb, vb, off, n_i, O, qo, logit, acc, NULL);
+                }
+            }
+    free(kb);
+    free(vb);
+    free(off);
+    free(logit);
+    free(acc);
+    return rc;
+}
+
 /* Dense baseline: Eq. 1 over raw tokens 0 .. T-1 of the full cache. */
 int kvo_dense_attention(int dtype, int L, int B, int H, int d, int T, int T_cap, const void *Q,
                         int Tq, const void *K, const void *V, void *O, double *probs,

@@ -181,6 +181,28 @@ def gated_attention(Q, K, V, Kbar, Vbar, idx, count, T, C, W, want_probs=False):
     return (O, probs) if want_probs else O
 
 
+def attention_ext(Q, K, V, T, C=1, W=0, Kbar=None, Vbar=None, idx=None, count=None, causal=0):
+    """Eq. 1 with grouped-query heads (K, V and the kept set have H_kv <= H heads) and, optionally,
+    a causal frame of queries (the Tq queries are the last Tq cached tokens).  Gated when Kbar is given."""
+    Q, K, V = (to_np(x) for x in (Q, K, V))
+    L, B, H, Tq, d = Q.shape
+    H_kv, T_cap = K.shape[2], K.shape[3]
+    gated = Kbar is not None
+    O = np.zeros_like(Q)
+    if gated:
+        Kbar, Vbar = to_np(Kbar), to_np(Vbar)
+        idx = np.ascontiguousarray(to_np(idx), dtype=np.int32)
+        count = np.ascontiguousarray(to_np(count), dtype=np.int32)
+        N_cap, k_cap = Kbar.shape[3], idx.shape[-1]
+    else:
+        N_cap, k_cap = 0, 0
+    rc = lib().kvo_attention_ext(dtype_code(Q), L, B, H, H_kv, d, T, T_cap, C, N_cap, W, int(gated), int(causal),
+                                 _p(Q), Tq, _p(K), _p(V), _p(Kbar) if gated else None, _p(Vbar) if gated else None,
+                                 _p(idx) if gated else None, _p(count) if gated else None, k_cap, _p(O))
+    _check(rc, "attention_ext")
+    return O
+
+
 def retain(Kbar_new, Vbar_new, util_new, first_chunk, n_new, k, Kc, Vc, chunk_id, util_c, count):
     """Physical eviction (sections 3.2-3.3): merge n_new freshly scored chunks into the compact
     store (Kc, Vc [...,k_cap,d], chunk_id, util_c [...,k_cap], count [...]), in place."""

@@ -504,6 +504,51 @@ def test_compact_attention_equals_gated_attention_on_the_gathered_rows(oracle):
         assert Kc.shape[3] - 1 + Kw.shape[3] == cfg.k + cfg.T - win0 < cfg.T
 
 
+def test_grouped_query_and_causal_attention(oracle):
+    """Grouped-query heads: the same as full multi-head attention on K, V (and kept sets) repeated per
+    group.  Causal frame: query i of the frame equals a single query attending a cache cut after its own
+    token, and the dense form equals the library's masked attention."""
+    cfg = TINY.replace(number=95, H=4, Tq=3, T=47)
+    t = _inputs(cfg)
+    r = oracle.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
+    # --- ext with H_kv == H and causal == 0 is the base function
+    O = oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T, cfg.C, cfg.W, r["Kbar"], r["Vbar"], r["idx"], r["count"])
+    assert (O == r["O"]).all()
+    assert (oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T) == oracle.dense_attention(t["Q"], t["K"], t["V"], cfg.T)).all()
+    # --- grouped: 2 kv heads serve 4 query heads
+    G = 2
+    K2, V2 = t["K"][:, :, ::G].contiguous(), t["V"][:, :, ::G].contiguous()
+    Kb2, Vb2 = np.ascontiguousarray(r["Kbar"][:, :, ::G]), np.ascontiguousarray(r["Vbar"][:, :, ::G])
+    i2, c2 = np.ascontiguousarray(r["idx"][:, :, ::G]), np.ascontiguousarray(r["count"][:, :, ::G])
+    Og = oracle.attention_ext(t["Q"], K2, V2, cfg.T, cfg.C, cfg.W, Kb2, Vb2, i2, c2)
+    rep = lambda a: np.repeat(oracle.to_np(a), G, axis=2)
+    Om = oracle.gated_attention(t["Q"], rep(K2), rep(V2), rep(Kb2), rep(Vb2), rep(i2), rep(c2), cfg.T, cfg.C, cfg.W)
+    assert (Og == Om).all()
+    assert (oracle.attention_ext(t["Q"], K2, V2, cfg.T) == oracle.dense_attention(t["Q"], rep(K2), rep(V2), cfg.T)).all()
+    # --- causal: query i == one query over the cache cut at its own position
+    Oc = oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T, cfg.C, cfg.W, r["Kbar"], r["Vbar"], r["idx"], r["count"], causal=1)
+    Od = oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T, causal=1)
+    n_cand = cfg.N_cand
+    for i in range(cfg.Tq):
+        Ti = cfg.T - cfg.Tq + 1 + i
+        qi = t["Q"][:, :, :, i:i + 1].contiguous()
+        # same candidates and window start as at length T: give the cut cache the window that keeps win0 fixed
+        Wi = Ti - n_cand * cfg.C
+        one = oracle.gated_attention(qi, t["K"], t["V"], r["Kbar"], r["Vbar"], r["idx"], r["count"], Ti, cfg.C, Wi)
+        assert (Oc[:, :, :, i] == one[:, :, :, 0]).all()
+        assert (Od[:, :, :, i] == oracle.dense_attention(qi, t["K"], t["V"], Ti)[:, :, :, 0]).all()
+    # the last query of a causal frame sees everything: equal to the non-causal result
+    assert (Oc[:, :, :, -1] == r["O"][:, :, :, -1]).all() and not (Oc[:, :, :, 0] == r["O"][:, :, :, 0]).all()
+    # --- dense causal vs the library, fp64, explicit mask
+    q, k, v = _f64(t["Q"]), _f64(t["K"])[..., :cfg.T, :], _f64(t["V"])[..., :cfg.T, :]
+    pos = torch.arange(cfg.T)[None, :] <= (cfg.T - cfg.Tq + torch.arange(cfg.Tq))[:, None]
+    want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=pos)
+    assert np.abs(Od - want.to(torch.float32).numpy()).max() < 1e-6
+    # a causal frame longer than the raw rows it sits in is refused
+    with pytest.raises(ValueError):
+        oracle.attention_ext(t["Q"], t["K"], t["V"], 2, causal=1)
+
+
 def test_edge_cases(oracle):
     cfg = TINY
     t = _inputs(cfg)
