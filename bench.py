@@ -391,6 +391,26 @@ def main():
                 "dense_hbm_frac": round(co3["dense"]["bytes"] / td / 1e3 / PEAK_HBM_GBS, 4),
                 "speedup_vs_dense": round(td / tg, 2)}
             del kv, s3, O3
+            torch.cuda.empty_cache()
+            # the same shape with the paper's 8 key-value heads (section 4.1): every row read serves 4 query heads
+            c3g = c3.replace(H_kv=8)
+            kvg = synth.make_qkv(c3g, dev)
+            s3g = kb.DecodeState(c3g)
+            s3g.Kbar.normal_(); s3g.Vbar.normal_()
+            u3g = torch.randn(s3g.util.shape, device=dev)
+            kb.kvev_select(s3g.shape, u3g, None, kb.SELECT_TOPK, c3g.k, 0.0, s3g.k_cap, s3g.idx, s3g.count)
+            O3g = torch.empty_like(kvg["Q"])
+            tgg = t_of(lambda: kb.kvev_gated_attention(s3g.shape, kvg["Q"], 1, kvg["K"], kvg["V"], s3g.Kbar, s3g.Vbar,
+                                                       s3g.idx, s3g.count, s3g.k_cap, O3g, s3g.ws), 20)
+            tdg = t_of(lambda: kb.kvev_dense_attention(s3g.shape, kvg["Q"], 1, kvg["K"], kvg["V"], O3g, s3g.ws), 5)
+            kv_frac = c3g.kv_heads / c3g.H
+            out["extra_cfg3_grouped_query"] = {
+                "workload": c3.name + " with 8 key-value heads for 32 query heads (grouped-query attention)",
+                "gated_us": round(tgg, 2), "gated_GBps_unique_rows": round(co3["attend"]["bytes"] * kv_frac / tgg / 1e3, 1),
+                "dense_us": round(tdg, 2), "dense_GBps_unique_rows": round(co3["dense"]["bytes"] * kv_frac / tdg / 1e3, 1),
+                "speedup_vs_dense": round(tdg / tgg, 2),
+                "gated_speedup_vs_32_kv_heads": round(tg / tgg, 2)}
+            del kvg, s3g, O3g
 
     # ---- CPU oracle on this host, same workload (whole problem for configs 1-2) ----
     if not args.no_cpu_baseline and not args.only:

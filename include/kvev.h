@@ -48,6 +48,10 @@ enum { KVEV_OP_CHUNK_POOL = 0, KVEV_OP_LSTM_GATE = 1, KVEV_OP_SELECT = 2,
  * (layer, batch row, head) triple, S = L*B*H of them, each independent.
  * T tokens are valid out of T_cap allocated per sequence; N_cap summary rows
  * are allocated per sequence (N_cap >= floor(T/C)).
+ * With H_kv key-value heads (H_kv divides H; section 4.1 names grouped-query
+ * attention) the caches, summaries, gate state, scores and kept sets exist per
+ * (layer, batch row, KV head), i.e. every [L,B,H,...] below except Q and O reads
+ * [L,B,H_kv,...], and query head h attends the cache of KV head h / (H / H_kv).
  * Supported: d in {64, 128}; dtype KVEV_F32 or KVEV_BF16; any C, W, d_sum, d_g
  * >= 1 (bf16 with d_sum % 32 == 0 and d_g % 64 == 0 takes the MFMA kernels). */
 typedef struct {
@@ -57,6 +61,7 @@ typedef struct {
     int32_t W;
     int32_t d_sum, d_g;
     int32_t dtype;
+    int32_t H_kv;      /* key-value heads (grouped-query attention); 0 means H */
 } kvev_shape;
 
 /* Aggregator MLP of Eq. 2, one set per layer (shared by batch rows and heads),
@@ -123,8 +128,11 @@ int kvev_select(const kvev_shape *shape, const float *util, const float *gate, i
  * n' = W + M).  For every sequence and each of its Tq queries the attended
  * rows are Kbar[idx[0..count)] / Vbar[...] followed by the raw tokens
  * win0 .. T-1 of K / V; O = softmax(q . keys^T / sqrt(d)) . values with fp32
- * scores, softmax and accumulation, rounded once to the storage dtype.  The
- * Tq queries see the whole cache and not each other (causal must be 0).
+ * scores, softmax and accumulation, rounded once to the storage dtype.  With
+ * causal == 0 the Tq queries see the whole cache and not each other; with
+ * causal == 1 (strict causality, section 3.2) they ARE the last Tq cached tokens,
+ * query i at position T - Tq + i, and each sees the kept summaries and the raw
+ * tokens up to and including its own position (needs Tq <= T - win0).
  * count == 0 (e.g. T <= W) is valid: the raw tokens alone are attended; no
  * rows at all gives O = 0.
  *   Q, O  [L,B,H,Tq,d]    idx [L,B,H,k_cap]   count [L,B,H], 0 <= count <= k_cap,

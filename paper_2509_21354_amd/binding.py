@@ -31,7 +31,7 @@ EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_atten
 
 class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("L", "B", "H", "d", "T", "T_cap", "C", "N_cap", "W", "d_sum", "d_g", "dtype")]
+                ("L", "B", "H", "d", "T", "T_cap", "C", "N_cap", "W", "d_sum", "d_g", "dtype", "H_kv")]
 
 
 class MlpW(ctypes.Structure):
@@ -106,7 +106,8 @@ def make_shape(cfg=None, **kw) -> Shape:
     v: Dict[str, int] = {}
     if cfg is not None:
         v.update(L=cfg.L, B=cfg.B, H=cfg.H, d=cfg.d, T=cfg.T, T_cap=cfg.T, C=cfg.C, N_cap=cfg.T // cfg.C,
-                 W=cfg.W, d_sum=cfg.d_sum, d_g=cfg.d_g, dtype=F32 if cfg.dtype == "f32" else BF16)
+                 W=cfg.W, d_sum=cfg.d_sum, d_g=cfg.d_g, dtype=F32 if cfg.dtype == "f32" else BF16,
+                 H_kv=getattr(cfg, "H_kv", 0))
     v.update(kw)
     return Shape(**v)
 
@@ -185,7 +186,7 @@ class DecodeState:
         self.N_cap = T_cap // cfg.C
         self.k_cap = cfg.k if k_cap is None else k_cap
         dt, dev = cfg.torch_dtype, device
-        lead = (cfg.L, cfg.B, cfg.H)
+        lead = (cfg.L, cfg.B, cfg.kv_heads)       # summaries, gate state and kept sets exist per key-value head
         self.Kbar = torch.zeros(lead + (self.N_cap, cfg.d), dtype=dt, device=dev)
         self.Vbar = torch.zeros_like(self.Kbar)
         self.h = torch.zeros(lead + (cfg.d_g,), dtype=torch.float32, device=dev)

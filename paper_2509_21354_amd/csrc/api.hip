@@ -29,10 +29,14 @@ static int check_shape(const kvev_shape *sh, bool chunked = true)
         return KVEV_ERR_INVALID_ARG;
     if (sh->T > sh->T_cap || (chunked && sh->T / sh->C > sh->N_cap)) return KVEV_ERR_INVALID_ARG;
     if ((int64_t)sh->L * sh->B * sh->H > (int64_t)1 << 24) return KVEV_ERR_INVALID_ARG;
+    if (sh->H_kv < 0 || (sh->H_kv > 0 && sh->H % sh->H_kv != 0)) return KVEV_ERR_INVALID_ARG;
     if (sh->dtype != KVEV_F32 && sh->dtype != KVEV_BF16) return KVEV_ERR_UNSUPPORTED;
     if (sh->d != 64 && sh->d != 128) return KVEV_ERR_UNSUPPORTED;
     return KVEV_OK;
 }
+
+// key-value heads: the caches, summaries, gate state and kept sets exist per (layer, batch row, KV head)
+static int kv_heads(const kvev_shape *sh) { return sh->H_kv > 0 ? sh->H_kv : sh->H; }
 
 static int n_cand_of(const kvev_shape *sh) { return (sh->T > sh->W ? sh->T - sh->W : 0) / sh->C; }
 
@@ -55,8 +59,12 @@ static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", 512);
 static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 {
     AttnPlan p;
+    // one workgroup serves up to 4 of the queries that share a key-value sequence
+    const int64_t R = (int64_t)(sh->H / kv_heads(sh)) * (Tq > 0 ? Tq : 1);
+    const int64_t qgroups = R >= 4 ? (R + 3) / 4 : R >= 2 ? (R + 1) / 2 : 1;
+    const int64_t units = (int64_t)sh->L * sh->B * kv_heads(sh) * qgroups;
     const int64_t sq = (int64_t)sh->L * sh->B * sh->H * (Tq > 0 ? Tq : 1);
-    int64_t want = (g_attn_target_blocks + sq - 1) / sq;
+    int64_t want = (g_attn_target_blocks + units - 1) / units;
     int64_t most = (n_rows + g_attn_min_rows - 1) / g_attn_min_rows;
     if (want > most) want = most;
     if (want < 1) want = 1;
@@ -69,7 +77,11 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
     return p;
 }
 
-static bool attn_takes_mq(const kvev_shape *sh, int Tq) { return sh->dtype == KVEV_BF16 && Tq >= 16; }
+// a frame of queries per key-value sequence (all heads of a group count) goes to the matrix cores
+static bool attn_takes_mq(const kvev_shape *sh, int Tq)
+{
+    return sh->dtype == KVEV_BF16 && (int64_t)(sh->H / kv_heads(sh)) * Tq >= 16;
+}
 
 static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
                             const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
@@ -85,7 +97,8 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     if (gated && (!Kbar || !Vbar || (!idx && !compact) || !count || k_cap < 0 || !aligned16(Kbar) || !aligned16(Vbar)))
         return KVEV_ERR_INVALID_ARG;
     if (gated && !compact && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
-    if (causal != 0) return KVEV_ERR_UNSUPPORTED;
+    if (causal != 0 && causal != 1) return KVEV_ERR_INVALID_ARG;
+    if (causal && compact) return KVEV_ERR_UNSUPPORTED;
     if (Tq == 0) return KVEV_OK;
     if ((int64_t)sh->L * sh->B * sh->H * Tq > (int64_t)1 << 26) return KVEV_ERR_INVALID_ARG;
 
@@ -93,6 +106,7 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     const int win0 = gated == 1 ? ncand * sh->C : 0;
     const int kmax = compact ? k_cap : gated ? (k_cap < ncand ? k_cap : ncand) : 0;
     const int n_rows = kmax + sh->T - win0;
+    if (causal && Tq > sh->T - win0) return KVEV_ERR_INVALID_ARG;      // the frame must lie inside the raw rows
     // a frame of queries on bf16 storage goes to the matrix-core kernel (no split, no scratch)
     const bool mq = attn_takes_mq(sh, Tq);
     const AttnPlan p = mq ? AttnPlan{1, n_rows, 0} : plan_attn(sh, Tq, n_rows);
@@ -101,7 +115,8 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     AttnArgs a;
     a.Q = Q; a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar; a.idx = idx; a.count = count; a.O = O;
     a.part = p.nsplit > 1 ? static_cast<float *>(ws) : nullptr;
-    a.S = sh->L * sh->B * sh->H; a.Tq = Tq; a.d = sh->d;
+    a.S = sh->L * sh->B * kv_heads(sh); a.Tq = Tq; a.d = sh->d;
+    a.G = sh->H / kv_heads(sh); a.Hkv = kv_heads(sh); a.causal = causal;
     a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = compact ? k_cap : sh->N_cap; a.k_cap = k_cap;
     a.win0 = win0; a.gated = gated ? 1 : 0;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
@@ -129,7 +144,7 @@ static size_t lstm_ws_pack(const kvev_shape *sh)
 static size_t lstm_ws_per_step(const kvev_shape *sh)
 {
     if (!lstm_takes_mfma(sh)) return 0;
-    const size_t groups = (size_t)sh->L * ((sh->B * sh->H + 15) / 16);
+    const size_t groups = (size_t)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
     return groups * 16 * 4 * sh->d_g * sizeof(float);
 }
 
@@ -159,7 +174,7 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
             return KVEV_ERR_UNSUPPORTED;
     }
     if (chunk_begin == chunk_end) return KVEV_OK;
-    if ((int64_t)sh->L * sh->B * sh->H * (chunk_end - chunk_begin) > (int64_t)1 << 30) return KVEV_ERR_INVALID_ARG;
+    if ((int64_t)sh->L * sh->B * kv_heads(sh) * (chunk_end - chunk_begin) > (int64_t)1 << 30) return KVEV_ERR_INVALID_ARG;
 
     PoolArgs a;
     memset(&a, 0, sizeof a);
@@ -168,7 +183,7 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
         a.W1K = wK->W1; a.b1K = wK->b1; a.W2K = wK->W2; a.b2K = wK->b2;
         a.W1V = wV->W1; a.b1V = wV->b1; a.W2V = wV->W2; a.b2V = wV->b2;
     }
-    a.L = sh->L; a.BH = sh->B * sh->H; a.d = sh->d; a.T_cap = sh->T_cap; a.C = sh->C; a.N_cap = sh->N_cap;
+    a.L = sh->L; a.BH = sh->B * kv_heads(sh); a.d = sh->d; a.T_cap = sh->T_cap; a.C = sh->C; a.N_cap = sh->N_cap;
     a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
     // bf16 storage with a hidden width the 16x16x32 tiling divides goes to the matrix cores
     const bool mfma = sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
@@ -198,7 +213,7 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
     a.Kbar = Kbar; a.Vbar = Vbar;
     a.W_ih = w->W_ih; a.W_hh = w->W_hh; a.b_ih = w->b_ih; a.b_hh = w->b_hh; a.w_s = w->w_s; a.b_s = w->b_s;
     a.h = h; a.c = c; a.util = util; a.gate = gate;
-    a.L = sh->L; a.BH = sh->B * sh->H; a.d = sh->d; a.N_cap = sh->N_cap; a.d_g = sh->d_g;
+    a.L = sh->L; a.BH = sh->B * kv_heads(sh); a.d = sh->d; a.N_cap = sh->N_cap; a.d_g = sh->d_g;
     a.c0 = chunk_begin; a.c1 = chunk_end;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -235,7 +250,7 @@ int kvev_select(const kvev_shape *sh, const float *util, const float *gate, int 
     }
     SelectArgs a;
     a.util = util; a.gate = gate; a.idx = idx; a.count = count;
-    a.S = sh->L * sh->B * sh->H; a.N_cap = sh->N_cap; a.n_cand = ncand; a.k = k; a.k_cap = k_cap;
+    a.S = sh->L * sh->B * kv_heads(sh); a.N_cap = sh->N_cap; a.n_cand = ncand; a.k = k; a.k_cap = k_cap;
     a.mode = mode; a.tau = tau;
     hipError_t e = launch_select(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
@@ -276,7 +291,7 @@ int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, co
     RetainArgs a;
     a.Kn = Kbar_new; a.Vn = Vbar_new; a.un = util_new; a.Kc = Kc; a.Vc = Vc; a.ids = chunk_id; a.uc = util_c;
     a.count = count;
-    a.S = sh->L * sh->B * sh->H;
+    a.S = sh->L * sh->B * kv_heads(sh);
     a.row_bytes = sh->d * (sh->dtype == KVEV_F32 ? 4 : 2);
     a.k = k; a.k_cap = k_cap; a.n_new_cap = n_new_cap; a.first_chunk = first_chunk; a.n_new = n_new;
     hipError_t e = launch_retain(a, static_cast<hipStream_t>(stream));

@@ -9,7 +9,8 @@
 // wave-level load is one contiguous 1 KiB piece of the cache.  Each lane group
 // keeps its own online-softmax state (m, l, o); the groups are merged by
 // shuffles, the waves through LDS, and the splits of one sequence by a second,
-// deterministic kernel (no float atomics).
+// deterministic kernel (no float atomics).  A workgroup serves up to 4 queries
+// that share the rows (the heads of a grouped-query group, a short frame).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -17,7 +18,19 @@ namespace kvev {
 
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for -inf: exp2(kNegBig - x) == 0, no NaN
 
-template <typename T, int D, int U>
+// Queries that share a key-value sequence: the Tq queries of each of the G query
+// heads of its group (grouped-query attention), numbered r = g * Tq + tq.  Row of
+// query r in Q / O [L,B,H,Tq,d] for key-value sequence s of [L,B,H_kv].
+__device__ __forceinline__ size_t query_row(const AttnArgs &a, int s, int r)
+{
+    const int g = r / a.Tq, tq = r - g * a.Tq;
+    const size_t head = (size_t)(s / a.Hkv) * ((size_t)a.Hkv * a.G) + (size_t)(s % a.Hkv) * a.G + g;
+    return head * a.Tq + tq;
+}
+
+// NQ queries of one key-value sequence per workgroup: every row that is loaded
+// serves all of them (what grouped-query heads and short query frames are for).
+template <typename T, int D, int U, int NQ>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
 {
     constexpr int EPL = D / 16;
@@ -25,9 +38,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
     const int wave = tid >> 6;
     const int grp = tid >> 4;      // row group within the workgroup, 0..15
     const int cl = tid & 15;       // column lane within the group
-    const int split = blockIdx.x % a.nsplit;
-    const int sq = blockIdx.x / a.nsplit;
-    const int s = sq / a.Tq;
+    const int R = a.G * a.Tq;
+    const int qgroups = (R + NQ - 1) / NQ;
+    int blk = blockIdx.x;
+    const int split = blk % a.nsplit; blk /= a.nsplit;
+    const int qg = blk % qgroups;
+    const int s = blk / qgroups;
 
     const T *K = static_cast<const T *>(a.K), *V = static_cast<const T *>(a.V);
     const T *Kbar = static_cast<const T *>(a.Kbar), *Vbar = static_cast<const T *>(a.Vbar);
@@ -38,18 +54,33 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
     const int j0 = split * a.rows_per_split;
     const int j1 = min(n, j0 + a.rows_per_split);
 
-    float qv[EPL];
-    {
-        Raw<T, EPL> r;
-        r.load(static_cast<const T *>(a.Q) + (size_t)sq * D + cl * EPL);
-        r.get(qv);
+    // per query: its row in Q / O and the first row it must not see (causal frame: the
+    // queries are the last Tq cached tokens and see nothing after their own position)
+    float qv[NQ][EPL];
+    size_t qrow[NQ];
+    int lim[NQ];
+    bool qok[NQ];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qv[e] *= a.scale_log2e;
+    for (int i = 0; i < NQ; ++i) {
+        const int r = qg * NQ + i;
+        qok[i] = r < R;
+        const int rc = qok[i] ? r : R - 1;
+        qrow[i] = query_row(a, s, rc);
+        lim[i] = qok[i] ? (a.causal ? n - (a.Tq - 1 - rc % a.Tq) : n) : 0;
+        Raw<T, EPL> raw;
+        raw.load(static_cast<const T *>(a.Q) + qrow[i] * D + cl * EPL);
+        raw.get(qv[i]);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qv[i][e] *= a.scale_log2e;
     }
 
-    float m = kNegBig, l = 0.f, o[EPL];
+    float m[NQ], l[NQ], o[NQ][EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+    for (int i = 0; i < NQ; ++i) {
+        m[i] = kNegBig; l[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[i][e] = 0.f;
+    }
 
     const size_t seq_raw = (size_t)s * a.T_cap;
     const size_t seq_sum = (size_t)s * a.N_cap;
@@ -57,12 +88,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
 
     for (int base = j0; base < j1; base += 16 * U) {
         Raw<T, EPL> kr[U], vr[U];
-        bool valid[U];
+        int jrow[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int j = base + grp + 16 * u;
-            valid[u] = j < j1;
-            j = valid[u] ? j : j1 - 1;
+            jrow[u] = j < j1 ? j : n;          // n: beyond every query's limit
+            j = j < j1 ? j : j1 - 1;
             size_t off;
             const T *kb, *vb;
             if (j < cnt) {
@@ -76,70 +107,90 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
             kr[u].load(kb + off + cl * EPL);
             vr[u].load(vb + off + cl * EPL);
         }
-        float sc[U];
-        float mx = kNegBig;
+        float sc[NQ][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float kv[EPL];
             kr[u].get(kv);
-            float d = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) d = fmaf(qv[e], kv[e], d);
-            d = group16_sum(d);
-            sc[u] = valid[u] ? d : kNegBig;
-            mx = fmaxf(mx, sc[u]);
+            for (int i = 0; i < NQ; ++i) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) d = fmaf(qv[i][e], kv[e], d);
+                d = group16_sum(d);
+                sc[i][u] = jrow[u] < lim[i] ? d : kNegBig;
+            }
         }
-        const float m_new = fmaxf(m, mx);
-        const float alpha = exp2f(m - m_new);
-        l *= alpha;
+        float alpha[NQ], p[NQ][U];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[e] *= alpha;
+        for (int i = 0; i < NQ; ++i) {
+            float mx = kNegBig;
+#pragma unroll
+            for (int u = 0; u < U; ++u) mx = fmaxf(mx, sc[i][u]);
+            const float m_new = fmaxf(m[i], mx);
+            alpha[i] = exp2f(m[i] - m_new);
+            l[i] *= alpha[i];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                p[i][u] = jrow[u] < lim[i] ? exp2f(sc[i][u] - m_new) : 0.f;
+                l[i] += p[i][u];
+            }
+            m[i] = m_new;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[i][e] *= alpha[i];
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float p = valid[u] ? exp2f(sc[u] - m_new) : 0.f;
             float vv[EPL];
             vr[u].get(vv);
-            l += p;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) o[e] = fmaf(p, vv[e], o[e]);
+            for (int i = 0; i < NQ; ++i)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[i][e] = fmaf(p[i][u], vv[e], o[i][e]);
         }
-        m = m_new;
     }
 
-    // merge the 4 lane groups of the wave
+    __shared__ float s_m[NQ][4], s_l[NQ][4], s_o[NQ][4][D];
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-        const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
-        const float M = fmaxf(m, m2);
-        const float a1 = exp2f(m - M), a2 = exp2f(m2 - M);
-        l = l * a1 + l2 * a2;
+    for (int i = 0; i < NQ; ++i) {
+        // merge the 4 lane groups of the wave
+        float mi = m[i], li = l[i];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[e] = o[e] * a1 + __shfl_xor(o[e], off) * a2;
-        m = M;
-    }
-
-    __shared__ float s_m[4], s_l[4], s_o[4][D];
-    if ((tid & 63) < 16) {
-        if (cl == 0) { s_m[wave] = m; s_l[wave] = l; }
+        for (int off = 16; off <= 32; off <<= 1) {
+            const float m2 = __shfl_xor(mi, off), l2 = __shfl_xor(li, off);
+            const float M = fmaxf(mi, m2);
+            const float a1 = exp2f(mi - M), a2 = exp2f(m2 - M);
+            li = li * a1 + l2 * a2;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s_o[wave][cl * EPL + e] = o[e];
+            for (int e = 0; e < EPL; ++e) o[i][e] = o[i][e] * a1 + __shfl_xor(o[i][e], off) * a2;
+            mi = M;
+        }
+        if ((tid & 63) < 16) {
+            if (cl == 0) { s_m[i][wave] = mi; s_l[i][wave] = li; }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) s_o[i][wave][cl * EPL + e] = o[i][e];
+        }
     }
     __syncthreads();
     if (tid < D) {
-        float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-        float L = 0.f, acc = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float f = exp2f(s_m[w] - M);
-            L += s_l[w] * f;
-            acc += s_o[w][tid] * f;
-        }
-        if (a.nsplit == 1) {
-            Storage<T>::store(static_cast<T *>(a.O) + (size_t)sq * D + tid, L > 0.f ? acc / L : 0.f);
-        } else {
-            float *p = a.part + ((size_t)sq * a.nsplit + split) * (D + 2);
-            p[tid] = acc;
-            if (tid == 0) { p[D] = M; p[D + 1] = L; }
+        for (int i = 0; i < NQ; ++i) {
+            if (!qok[i]) continue;
+            const float M = fmaxf(fmaxf(s_m[i][0], s_m[i][1]), fmaxf(s_m[i][2], s_m[i][3]));
+            float L = 0.f, acc = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = exp2f(s_m[i][w] - M);
+                L += s_l[i][w] * f;
+                acc += s_o[i][w][tid] * f;
+            }
+            if (a.nsplit == 1) {
+                Storage<T>::store(static_cast<T *>(a.O) + qrow[i] * D + tid, L > 0.f ? acc / L : 0.f);
+            } else {
+                float *pp = a.part + (((size_t)s * R + (qg * NQ + i)) * a.nsplit + split) * (D + 2);
+                pp[tid] = acc;
+                if (tid == 0) { pp[D] = M; pp[D + 1] = L; }
+            }
         }
     }
 }
@@ -149,7 +200,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
 // splits' maxima and sums are reduced across the workgroup first, so that the
 // D-wide accumulation only issues independent loads.
 template <typename T, int D>
-__global__ __launch_bounds__(D) void attn_combine_kernel(const float *part, int nsplit, T *O)
+__global__ __launch_bounds__(D) void attn_combine_kernel(AttnArgs a, const float *part, int nsplit, T *O)
 {
     extern __shared__ float s_w[];                 // [nsplit] weights exp2(m_i - M)
     __shared__ float s_red[2][D / 64];
@@ -188,20 +239,31 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float *part, int 
         for (int u = 0; u < 8; ++u) acc = fmaf(v[u], s_w[i + u], acc);
     }
     for (; i < nsplit; ++i) acc = fmaf(p[(size_t)i * (D + 2) + t], s_w[i], acc);
-    Storage<T>::store(O + (size_t)sq * D + t, L > 0.f ? acc / L : 0.f);
+    const int R = a.G * a.Tq;
+    Storage<T>::store(O + query_row(a, sq / R, sq % R) * D + t, L > 0.f ? acc / L : 0.f);
+}
+
+template <typename T, int D, int NQ>
+static hipError_t launch_decode_q(const AttnArgs &a, hipStream_t st)
+{
+    constexpr int U = NQ >= 4 ? 2 : 4;       // rows in flight per lane group: fewer when more queries hold registers
+    const int R = a.G * a.Tq;
+    const size_t blocks = (size_t)a.S * ((R + NQ - 1) / NQ) * a.nsplit;
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (a.nsplit > 1)
+        hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * R)), dim3(D),
+                           (size_t)a.nsplit * sizeof(float), st, a, a.part, a.nsplit, static_cast<T *>(a.O));
+    return hipGetLastError();
 }
 
 template <typename T, int D>
 static hipError_t launch_decode_t(const AttnArgs &a, hipStream_t st)
 {
-    constexpr int U = 4;
-    const unsigned blocks = (unsigned)((size_t)a.S * a.Tq * a.nsplit);
-    if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_decode_kernel<T, D, U>), dim3(blocks), dim3(256), 0, st, a);
-    if (a.nsplit > 1)
-        hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * a.Tq)), dim3(D),
-                           (size_t)a.nsplit * sizeof(float), st, a.part, a.nsplit, static_cast<T *>(a.O));
-    return hipGetLastError();
+    const int R = a.G * a.Tq;
+    if (R >= 4) return launch_decode_q<T, D, 4>(a, st);
+    if (R >= 2) return launch_decode_q<T, D, 2>(a, st);
+    return launch_decode_q<T, D, 1>(a, st);
 }
 
 hipError_t launch_attn_decode(const AttnArgs &a, int dtype, hipStream_t st)

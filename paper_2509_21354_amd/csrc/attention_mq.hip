@@ -74,12 +74,20 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
     }
 
     // queries of this wave: sub-tile u holds query qt*BM + wave*16*QS + u*16 + n
+    // (queries that share the sequence: the Tq queries of each of the G heads of its group, r = g*Tq + tq)
     bf16x8_t qf[QS][KS];
-    int qrow[QS];
+    int qrow[QS], lim[QS];
+    size_t orow[QS];
+    const int R = a.G * a.Tq;
 #pragma unroll
     for (int u = 0; u < QS; ++u) {
         qrow[u] = qt * BM + (wave * QS + u) * 16 + n;
-        const bf16_t *Qp = static_cast<const bf16_t *>(a.Q) + ((size_t)s * a.Tq + min(qrow[u], a.Tq - 1)) * D + g * 8;
+        const int rc = min(qrow[u], R - 1);
+        const int gq = rc / a.Tq, tq = rc - gq * a.Tq;
+        orow[u] = ((size_t)(s / a.Hkv) * ((size_t)a.Hkv * a.G) + (size_t)(s % a.Hkv) * a.G + gq) * a.Tq + tq;
+        // causal frame: the queries are the last Tq cached tokens; rows after a query's own token are hidden
+        lim[u] = a.causal ? nrows - (a.Tq - 1 - tq) : nrows;
+        const bf16_t *Qp = static_cast<const bf16_t *>(a.Q) + orow[u] * D + g * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[u][ks] = *reinterpret_cast<const bf16x8_t *>(Qp + ks * 32);
     }
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
         }
         __syncthreads();
         if (j0 + BN < nrows) { KVEV_MQ_FETCH(j0 + BN) }   // next tile's copy rides under this tile's math
-        const bool full = j0 + BN <= nrows;
+        const bool full = j0 + BN <= nrows - (a.causal ? a.Tq - 1 : 0);    // no row of the tile is hidden from any query
 
 #pragma unroll
         for (int u = 0; u < QS; ++u) {
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        if (j0 + kt * 16 + 4 * g + r >= nrows) st[kt][r] = kNegBigMq;
+                        if (j0 + kt * 16 + 4 * g + r >= lim[u]) st[kt][r] = kNegBigMq;
             }
             float mx = kNegBigMq;
 #pragma unroll
@@ -180,9 +188,9 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
         float l = lsum[u];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        if (qrow[u] < a.Tq) {
+        if (qrow[u] < R) {
             const float inv = l > 0.f ? 1.0f / l : 0.f;
-            bf16_t *Op = static_cast<bf16_t *>(a.O) + ((size_t)s * a.Tq + qrow[u]) * D + 4 * g;
+            bf16_t *Op = static_cast<bf16_t *>(a.O) + orow[u] * D + 4 * g;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 uint2 w;
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
 template <int D, int QS>
 static hipError_t launch_mq_t(const AttnArgs &a, hipStream_t st)
 {
-    const int qtiles = (a.Tq + 64 * QS - 1) / (64 * QS);
+    const int qtiles = (a.G * a.Tq + 64 * QS - 1) / (64 * QS);
     const size_t blocks = (size_t)a.S * qtiles;
     if (blocks == 0) return hipSuccess;
     hipLaunchKernelGGL((attn_mq_kernel<D, QS>), dim3((unsigned)blocks), dim3(256), 0, st, a, qtiles, (int)blocks);
@@ -210,7 +218,7 @@ hipError_t launch_attn_mq(const AttnArgs &a, hipStream_t st)
 {
     // 128 queries per workgroup halve the LDS traffic per flop; frames shorter than
     // that would leave half the waves idle
-    const bool wide = a.Tq > 64;
+    const bool wide = a.G * a.Tq > 64;
     if (a.d == 64) return wide ? launch_mq_t<64, 2>(a, st) : launch_mq_t<64, 1>(a, st);
     return wide ? launch_mq_t<128, 2>(a, st) : launch_mq_t<128, 1>(a, st);
 }

@@ -54,6 +54,11 @@ class Config:
     steps: int = 1      # streaming steps (frames appended); 1 = one-shot
     frame: int = 0      # tokens appended per streaming step
     decode_per_step: int = 1
+    H_kv: int = 0       # key-value heads (grouped-query attention); 0 = H
+
+    @property
+    def kv_heads(self) -> int:
+        return self.H_kv or self.H
 
     @property
     def N(self) -> int:
@@ -136,14 +141,14 @@ def make_weights(cfg: Config, device="cpu") -> Dict[str, torch.Tensor]:
 
 
 def make_qkv(cfg: Config, device="cpu", T_cap: int | None = None) -> Dict[str, torch.Tensor]:
-    """Q [L,B,H,Tq,d]; K, V [L,B,H,T_cap,d] with the first T tokens drawn (the
+    """Q [L,B,H,Tq,d]; K, V [L,B,H_kv,T_cap,d] with the first T tokens drawn (the
     rest, if T_cap > T, is filled from the same stream: never read by the path)."""
     T_cap = cfg.T if T_cap is None else T_cap
     dt = cfg.torch_dtype
     out = {
         "Q": _normal((cfg.L, cfg.B, cfg.H, cfg.Tq, cfg.d), dt, device, seed_of(cfg, "Q")),
-        "K": _normal((cfg.L, cfg.B, cfg.H, T_cap, cfg.d), dt, device, seed_of(cfg, "K")),
-        "V": _normal((cfg.L, cfg.B, cfg.H, T_cap, cfg.d), dt, device, seed_of(cfg, "V")),
+        "K": _normal((cfg.L, cfg.B, cfg.kv_heads, T_cap, cfg.d), dt, device, seed_of(cfg, "K")),
+        "V": _normal((cfg.L, cfg.B, cfg.kv_heads, T_cap, cfg.d), dt, device, seed_of(cfg, "V")),
     }
     return out
 

@@ -58,7 +58,11 @@ def test_pointer_range_and_mode_validation():
     assert L.kvev_dense_attention(r, None, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_dense_attention(r, odd, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_dense_attention(r, FAKE, -1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
-    assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 1, FAKE, None, 0, None) == kb.ERR_UNSUPPORTED
+    assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 2, FAKE, None, 0, None) == kb.ERR_INVALID_ARG      # causal is 0 or 1
+    assert L.kvev_dense_attention(r, FAKE, 5000, FAKE, FAKE, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # frame longer than the cache
+    assert L.kvev_gated_attention(r, FAKE, 400, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG  # frame outside the raw window
+    bad_kv = _shape(H_kv=5)
+    assert L.kvev_dense_attention(ctypes.byref(bad_kv), FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.ERR_WORKSPACE
     assert L.kvev_dense_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, 64, None) == kb.ERR_WORKSPACE
     assert L.kvev_dense_attention(r, FAKE, 0, FAKE, FAKE, 0, FAKE, None, 0, None) == kb.OK   # Tq = 0: nothing to do
