@@ -31,15 +31,18 @@ namespace kvev {
 constexpr float kNegBigMq = -1.0e30f;
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 typedef v4i16_t __attribute__((address_space(3))) lds_v4i16_t;
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // a 16-byte piece in flight
 
 template <int D, int QS>
 __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles, int nblocks)
 {
     constexpr int BN = 64, RP = D + 8, KS = D / 32, DT = D / 16, BM = 64 * QS;
+    // V rows are padded by 32 bytes: the transposing load has 16 lanes read 8 bytes each from 4 consecutive
+    // rows, and a row pitch of 8 banks (mod 64) puts those 16 pieces in 16 different bank pairs; the 16-byte
+    // row reads of K want the 16-byte padding instead
+    constexpr int RPV = D + 16;
     constexpr int CPT = BN * (D / 8) / 256;          // 16-byte chunks per thread per tile, for K and for V
     __shared__ __align__(16) bf16_t s_k[BN * RP];    // row-major, padded rows
-    __shared__ __align__(16) bf16_t s_v[BN * RP];
+    __shared__ __align__(16) bf16_t s_v[BN * RPV];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
@@ -73,6 +76,24 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
         vreg[i] = *reinterpret_cast<const u32x4_t *>((sm ? Vbar : V) + off);                             \
     }
 
+    // Tiles that hold raw rows only (all of them for the dense baseline, all but the first one or two
+    // otherwise) are fetched through buffer descriptors: one lane offset for all loads, the tile and row
+    // step in a scalar register; rows past the end read as zeros (they are masked in the softmax).
+    const size_t raw_rows = (size_t)(a.T - a.win0);
+    const bool fast = raw_rows * D * sizeof(bf16_t) < ((size_t)1 << 32);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(K + (seq_raw + a.win0) * D, (uint32_t)(raw_rows * D * sizeof(bf16_t)));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(V + (seq_raw + a.win0) * D, (uint32_t)(raw_rows * D * sizeof(bf16_t)));
+    const uint32_t voff = (uint32_t)((sr * D + dc * 8) * sizeof(bf16_t));
+#define KVEV_MQ_FETCH_RAW(J0)                                                                          \
+    _Pragma("unroll") for (int i = 0; i < CPT; ++i)                                                    \
+    {                                                                                                  \
+        const uint32_t soff = (uint32_t)(((J0) - cnt + RSTEP * i) * D * (int)sizeof(bf16_t));          \
+        kreg[i] = buffer_load16<u32x4_t>(rk, voff, soff);                                              \
+        vreg[i] = buffer_load16<u32x4_t>(rv, voff, soff);                                              \
+    }
+#define KVEV_MQ_FETCH_ANY(J0)                                                                          \
+    if (fast && (J0) >= cnt) { KVEV_MQ_FETCH_RAW(J0) } else { KVEV_MQ_FETCH(J0) }
+
     // queries of this wave: sub-tile u holds query qt*BM + wave*16*QS + u*16 + n
     // (queries that share the sequence: the Tq queries of each of the G heads of its group, r = g*Tq + tq)
     bf16x8_t qf[QS][KS];
@@ -103,43 +124,48 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
     }
     const float c = a.scale_log2e;
 
-    if (nrows > 0) { KVEV_MQ_FETCH(0) }
+    if (nrows > 0) { KVEV_MQ_FETCH_ANY(0) }
     for (int j0 = 0; j0 < nrows; j0 += BN) {
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             *reinterpret_cast<u32x4_t *>(s_k + (size_t)(sr + RSTEP * i) * RP + dc * 8) = kreg[i];
-            *reinterpret_cast<u32x4_t *>(s_v + (size_t)(sr + RSTEP * i) * RP + dc * 8) = vreg[i];
+            *reinterpret_cast<u32x4_t *>(s_v + (size_t)(sr + RSTEP * i) * RPV + dc * 8) = vreg[i];
         }
         __syncthreads();
-        if (j0 + BN < nrows) { KVEV_MQ_FETCH(j0 + BN) }   // next tile's copy rides under this tile's math
+        if (j0 + BN < nrows) { KVEV_MQ_FETCH_ANY(j0 + BN) }   // next tile's copy rides under this tile's math
         const bool full = j0 + BN <= nrows - (a.causal ? a.Tq - 1 : 0);    // no row of the tile is hidden from any query
 
+        // ---- S^T = K Q^T: every K fragment read from LDS serves all QS query sub-tiles of the wave ----
+        f32x4_t st[QS][4];
+#pragma unroll
+        for (int u = 0; u < QS; ++u)
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) st[u][kt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(s_k + (size_t)(kt * 16 + n) * RP + ks * 32 + g * 8);
+#pragma unroll
+                for (int u = 0; u < QS; ++u)
+                    st[u][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[u][ks], st[u][kt], 0, 0, 0);
+            }
+        // ---- online softmax for this lane's queries (raw scores; scale folded into exp2) ----
+        bf16x8_t pb[QS][2];
 #pragma unroll
         for (int u = 0; u < QS; ++u) {
-            // ---- S^T = K Q^T ------------------------------------------------------
-            f32x4_t st[4];
-#pragma unroll
-            for (int kt = 0; kt < 4; ++kt) st[kt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt) {
-                    const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(s_k + (size_t)(kt * 16 + n) * RP + ks * 32 + g * 8);
-                    st[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[u][ks], st[kt], 0, 0, 0);
-                }
-            // ---- online softmax for this lane's query (raw scores; scale folded into exp2) ----
             if (!full) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        if (j0 + kt * 16 + 4 * g + r >= lim[u]) st[kt][r] = kNegBigMq;
+                        if (j0 + kt * 16 + 4 * g + r >= lim[u]) st[u][kt][r] = kNegBigMq;
             }
             float mx = kNegBigMq;
 #pragma unroll
             for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, st[kt][r]);
+                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, st[u][kt][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m[u], mx);
@@ -153,33 +179,34 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
                 m[u] = m_new;
             }
             const float mc = -m_new * c;
-            bf16x8_t pb[2];
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
                 float p[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = __builtin_amdgcn_exp2f(fmaf(st[2 * h2 + (e >> 2)][e & 3], c, mc));   // masked: exp2(-huge) = 0
+                    p[e] = __builtin_amdgcn_exp2f(fmaf(st[u][2 * h2 + (e >> 2)][e & 3], c, mc));   // masked: exp2(-huge) = 0
                     lsum[u] += p[e];
                 }
-                pb[h2] = __builtin_bit_cast(bf16x8_t, make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
-                                                                  pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])));
+                pb[u][h2] = __builtin_bit_cast(bf16x8_t, make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
+                                                                     pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])));
             }
-            // ---- O^T += V^T P^T ---------------------------------------------------
-            // transposing load: source lane i of a 16-lane block points at key 4g + i/4,
-            // d = 16 dt + 4 (i%4) .. +3; destination lane i receives d = 16 dt + i of keys
-            // 4g .. 4g+3.  The second load does the same 16 keys further (registers e >= 4).
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const bf16_t *src = s_v + (size_t)(h2 * 32 + 4 * g + (n >> 2)) * RP + dt * 16 + 4 * (n & 3);
-                    const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t *)src);
-                    const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t *)(src + 16 * RP));
-                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                    o[u][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[h2], o[u][dt], 0, 0, 0);
-                }
         }
+        // ---- O^T += V^T P^T: every V^T fragment serves all QS sub-tiles ----------------
+        // transposing load: source lane i of a 16-lane block points at key 4g + i/4,
+        // d = 16 dt + 4 (i%4) .. +3; destination lane i receives d = 16 dt + i of keys
+        // 4g .. 4g+3.  The second load does the same 16 keys further (registers e >= 4).
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const bf16_t *src = s_v + (size_t)(h2 * 32 + 4 * g + (n >> 2)) * RPV + dt * 16 + 4 * (n & 3);
+                const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t *)src);
+                const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t *)(src + 16 * RPV));
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int u = 0; u < QS; ++u)
+                    o[u][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[u][h2], o[u][dt], 0, 0, 0);
+            }
         __syncthreads();
     }
 
@@ -203,6 +230,8 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
 }
 
 #undef KVEV_MQ_FETCH
+#undef KVEV_MQ_FETCH_RAW
+#undef KVEV_MQ_FETCH_ANY
 
 template <int D, int QS>
 static hipError_t launch_mq_t(const AttnArgs &a, hipStream_t st)

@@ -43,21 +43,6 @@ __device__ __forceinline__ float tanh_hw(float x)
     return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
 }
 
-// 16-byte load through a buffer descriptor: address = descriptor base (SGPRs) +
-// voff (one VGPR, shared by every load of the lane) + soff (SGPR or constant),
-// with the constant part of voff folded into the instruction's immediate.  Keeps
-// the many weight-fragment addresses of the recurrence out of the vector registers.
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00027000);
-}
-template <typename V> __device__ __forceinline__ V buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff)
-{
-    const u32x4_t raw = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, (int)soff, 0);
-    return __builtin_bit_cast(V, raw);
-}
-
 constexpr int kTT = 4;   // steps per wave pass of the input projection
 
 // Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
