@@ -18,16 +18,27 @@
 // other (4 live accumulators), which leaves the registers to a deep ring of
 // prefetched weight fragments.
 //
-// The state h is fp32.  To feed it to the bf16 matrix cores without losing it,
-// h is cut into three bf16 terms (h = hi + mid + lo, exact to 24 bits) and the
-// product is taken once per term; every partial product is exact and the sum
-// is accumulated in fp32, so the result has fp32 accuracy.
+// The state h is fp32 and the weights are bf16.  To feed the product W_hh h to the
+// matrix cores without losing the state's precision, both go to fp16 operands:
+//   * W_hh times a per-layer power of two s that lifts its largest magnitude to
+//     [2^14, 2^15): a bf16 value has 8 significant bits, fp16 holds 11 and keeps
+//     subnormals (checked on the device), so s*w is exact for every weight down to
+//     2^-31 of the largest one (below that the rounding error is < 2^-39 of the
+//     largest weight: far under the fp32 accumulation's own);
+//   * h = hi + lo with hi = fp16(h), lo = fp16(h - hi): 22 significant bits (|h| < 1,
+//     absolute error <= max(2^-22 |h|, 2^-25)).
+// An fp16 x fp16 product has 22 bits and is exact in the fp32 accumulator, so two
+// MFMAs per weight fragment give an fp32-grade W_hh h (three would be needed with
+// bf16 terms); the result is scaled back by 1/s, exactly.
 #include "common.hpp"
 #include "kernels.hpp"
 #include <utility>
 
 
 namespace kvev {
+
+typedef _Float16 f16_t;
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 
 // Gate nonlinearities through the hardware exp2 and reciprocal (about 1 ulp
 // each).  Their absolute error stays below ~2e-7 everywhere, which is what the
@@ -82,21 +93,24 @@ template <int DG> struct Res {
     static constexpr int cls(int i)
     {
         if (DG <= 128) return 0;
-        if (DG == 256) return i % 2 != 0 ? 2 : i % 6 == 0 ? 0 : 1;     // of 16: 3 in LDS, 5 in registers, 8 streamed
+        if (DG == 256) {                       // of 16: 3 in LDS, 7 in registers, 6 streamed
+            constexpr int t[16] = {0, 1, 2, 1, 1, 2, 0, 1, 2, 1, 1, 2, 0, 1, 2, 2};
+            return t[i];
+        }
         return 2;
     }
     static constexpr int count(int c) { int k = 0; for (int i = 0; i < ITEMS; ++i) k += cls(i) == c; return k; }
     static constexpr int idx(int i) { int k = 0; for (int j = 0; j < i; ++j) k += cls(j) == cls(i); return k; }   // rank within its class
     static constexpr int pos(int c, int k) { for (int i = 0; i < ITEMS; ++i) if (cls(i) == c && idx(i) == k) return i; return 0; }
     static constexpr int LRES = count(0), RRES = count(1), NS = count(2);
-    static constexpr int NSLOT = NS == 0 ? 1 : DG == 256 ? 4 : 8;
+    static constexpr int NSLOT = NS == 0 ? 1 : DG == 256 ? 3 : 8;
     static constexpr int PF = NSLOT - 1;
     static_assert(NS % NSLOT == 0, "slot rotation must line up with the item loop");
     // register buffers for LDS items, read one item ahead: two when LDS items follow each other
     static constexpr bool lds_adjacent() { for (int i = 0; i < ITEMS; ++i) if (cls(i) == 0 && cls((i + 1) % ITEMS) == 0) return true; return false; }
     static constexpr int NWL = lds_adjacent() ? 2 : 1;
     static_assert(NWL == 1 || LRES % 2 == 0, "buffer parity must survive the wrap into the next step");
-    static constexpr size_t lds_h = (size_t)2 * 3 * 16 * (DG + 8) * sizeof(bf16_t);
+    static constexpr size_t lds_h = (size_t)2 * 2 * 16 * (DG + 8) * sizeof(f16_t);      // 2 buffers x (hi, lo) planes
     static constexpr size_t lds_up = (size_t)2 * G::NW * 16 * sizeof(float);
     static constexpr size_t lds_w = (size_t)G::NW * LRES * 4096;
     static constexpr size_t lds = lds_h + lds_up + lds_w;
@@ -178,12 +192,44 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
     }
 }
 
-// W_hh re-laid in A-fragment order so that every wave-level load of the
-// recurrence is one contiguous 1 KiB piece (the row-major matrix would give 16
-// half-used cache lines per load): [layer][wave][item][gate][lane][8], items in
-// the order the wave walks them.
+// Per layer: the power of two s that lifts max |W_hh| into [2^14, 2^15) and its
+// inverse, scale[2l] = s, scale[2l+1] = 1/s (s = 1 for an all-zero matrix).
+__global__ __launch_bounds__(1024) void lstm_whh_scale_kernel(const bf16_t *W_hh, size_t per_layer, float *scale)
+{
+    __shared__ float s_max[16];
+    const int l = blockIdx.x, t = threadIdx.x;
+    const bf16_t *W = W_hh + (size_t)l * per_layer;
+    float m = 0.f;
+    for (size_t i = (size_t)t * 8; i < per_layer; i += 1024 * 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(W + i);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float lo = fabsf(__uint_as_float(w[j] << 16)), hi = fabsf(__uint_as_float(w[j] & 0xFFFF0000u));
+            m = fmaxf(m, (lo == lo && lo < INFINITY) ? lo : 0.f);       // a NaN or infinite weight takes no part
+            m = fmaxf(m, (hi == hi && hi < INFINITY) ? hi : 0.f);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((t & 63) == 0) s_max[t >> 6] = m;
+    __syncthreads();
+    if (t == 0) {
+        for (int w = 1; w < 16; ++w) m = fmaxf(m, s_max[w]);
+        int k = 0;
+        if (m > 0.f) k = 14 - ilogbf(m);
+        k = k > 100 ? 100 : k < -100 ? -100 : k;
+        scale[2 * l] = ldexpf(1.f, k);
+        scale[2 * l + 1] = ldexpf(1.f, -k);
+    }
+}
+
+// W_hh scaled, converted to fp16 and re-laid in A-fragment order so that every
+// wave-level load of the recurrence is one contiguous 1 KiB piece (the row-major
+// matrix would give 16 half-used cache lines per load):
+// [layer][wave][item][gate][lane][8], items in the order the wave walks them.
 template <int DG>
-__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, bf16x8_t *packed, int L)
+__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, f16x8_t *packed, const float *scale, int L)
 {
     using G = Geo<DG>;
     constexpr int NW = G::NW, UT = G::UT;
@@ -199,7 +245,16 @@ __global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, 
     const int l = (int)(r / NW);
     const int n = lane & 15, g4 = lane >> 4;
     const bf16_t *src = W_hh + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * DG + ks * 32 + g4 * 8;
-    packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
+    const uint4 v = *reinterpret_cast<const uint4 *>(src);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const float sc = scale[2 * l];
+    f16x8_t o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        o[2 * j] = (f16_t)(__uint_as_float(w[j] << 16) * sc);
+        o[2 * j + 1] = (f16_t)(__uint_as_float(w[j] & 0xFFFF0000u) * sc);
+    }
+    packed[frag] = o;
 }
 
 // W_ih in A-fragment order for the input projection: [layer][wave][unit tile][gate][k-step][lane][8].
@@ -230,7 +285,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
     constexpr int NW = G::NW, KS = G::KS, UT = G::UT, ITEMS = G::ITEMS, HP = DG + 8;
     constexpr int LRES = R::LRES, RRES = R::RRES, NS = R::NS, NSLOT = R::NSLOT, PF = R::PF, NWL = R::NWL;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16_t *s_h = reinterpret_cast<bf16_t *>(smem_raw);                                   // [2][3][16][HP]
+    f16_t *s_h = reinterpret_cast<f16_t *>(smem_raw);                                     // [2][2][16][HP]: buffer, (hi, lo)
     float *s_up = reinterpret_cast<float *>(smem_raw + R::lds_h);                         // [2][NW][16]
     unsigned char *s_w = smem_raw + R::lds_h + R::lds_up;                                 // [NW][LRES] items of 4 KiB
 
@@ -246,6 +301,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 
     const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
     const float b_s = bf16_to_f32(static_cast<const bf16_t *>(a.b_s)[l]);
+    const float inv_scale = a.whh_scale[2 * l + 1];      // undoes the power-of-two scaling of the packed W_hh
 
     // state of (sequence n, units 16*UT*wave + 16*ut + 4*g4 + r) lives in this lane
     float c_reg[UT][4], h_reg[UT][4], ws_reg[UT][4];
@@ -266,28 +322,21 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
     const uint32_t lane16 = lane * 16;
     const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wbase, ITEMS * 4096);
     const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * NW * UT * 4096 - (uint32_t)wave * UT * 4096);
-    bf16_t *h_wr = s_h + (size_t)n * HP + wave * 16 * UT + 4 * g4;          // + (buf*3+p)*16*HP + ut*16
-    const bf16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;                // + (buf*3+p)*16*HP + ks*32
+    f16_t *h_wr = s_h + (size_t)n * HP + wave * 16 * UT + 4 * g4;           // + (buf*2+p)*16*HP + ut*16
+    const f16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;                 // + (buf*2+p)*16*HP + ks*32
     unsigned char *w_lds = s_w + (size_t)wave * LRES * 4096 + lane16;  // + k*4096 + q*1024 for the wave's k-th LDS item
 
+    // h leaves the registers as two fp16 terms (hi + lo = h to 22 bits)
     auto publish_h = [&](int buf, int ut, const float (&hv)[4]) {
-        float hi[4], mid[4], lo[4];
+        typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+        f16x4_t hi, lo;
 #pragma unroll
-        for (int r = 0; r < 4; r += 2) {
-            const uint32_t ph = pack_bf16x2(hv[r], hv[r + 1]);
-            hi[r] = __uint_as_float(ph << 16); hi[r + 1] = __uint_as_float(ph & 0xFFFF0000u);
-            const float r0 = hv[r] - hi[r], r1 = hv[r + 1] - hi[r + 1];
-            const uint32_t pm = pack_bf16x2(r0, r1);
-            mid[r] = __uint_as_float(pm << 16); mid[r + 1] = __uint_as_float(pm & 0xFFFF0000u);
-            lo[r] = r0 - mid[r]; lo[r + 1] = r1 - mid[r + 1];
+        for (int r = 0; r < 4; ++r) {
+            hi[r] = (f16_t)hv[r];
+            lo[r] = (f16_t)(hv[r] - (float)hi[r]);
         }
-        uint2 v;
-        v.x = pack_bf16x2(hi[0], hi[1]); v.y = pack_bf16x2(hi[2], hi[3]);
-        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 0) * 16 * HP + ut * 16) = v;
-        v.x = pack_bf16x2(mid[0], mid[1]); v.y = pack_bf16x2(mid[2], mid[3]);
-        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 1) * 16 * HP + ut * 16) = v;
-        v.x = pack_bf16x2(lo[0], lo[1]); v.y = pack_bf16x2(lo[2], lo[3]);
-        *reinterpret_cast<uint2 *>(h_wr + (size_t)(buf * 3 + 2) * 16 * HP + ut * 16) = v;
+        *reinterpret_cast<f16x4_t *>(h_wr + (size_t)(buf * 2 + 0) * 16 * HP + ut * 16) = hi;
+        *reinterpret_cast<f16x4_t *>(h_wr + (size_t)(buf * 2 + 1) * 16 * HP + ut * 16) = lo;
     };
 
     // ---- resident items: LDS and registers, filled once ------------------------
@@ -295,38 +344,38 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
         constexpr int k = decltype(kc)::value, i = R::pos(0, k);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<bf16x8_t *>(w_lds + k * 4096 + q * 1024) = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
+            *reinterpret_cast<f16x8_t *>(w_lds + k * 4096 + q * 1024) = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
     });
-    bf16x8_t wres[RRES > 0 ? RRES : 1][4];
+    f16x8_t wres[RRES > 0 ? RRES : 1][4];
     static_for<RRES>([&](auto kc) {
         constexpr int k = decltype(kc)::value, i = R::pos(1, k);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            wres[k][q] = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
+            wres[k][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
     });
     // ---- streamed items: the ring runs PF items ahead and wraps into the next step,
     // so the cell update and the barrier overlap with loads already in flight ----
-    bf16x8_t wbuf[NSLOT][4];
+    f16x8_t wbuf[NSLOT][4];
     auto load_w = [&](auto jc) {               // jc: index within the streamed items
         constexpr int j = decltype(jc)::value, i = R::pos(2, j);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            wbuf[j % NSLOT][q] = buffer_load16<bf16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
+            wbuf[j % NSLOT][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, i * 4096);
     };
     if constexpr (NS > 0) static_for<PF>(load_w);
     // LDS items pass through a register buffer that is read one item ahead
-    bf16x8_t wl[NWL][4];
+    f16x8_t wl[NWL][4];
     auto read_wl = [&](auto kc) {              // kc: index within the LDS items
         constexpr int k = decltype(kc)::value;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) wl[k % NWL][q] = *reinterpret_cast<const bf16x8_t *>(w_lds + k * 4096 + q * 1024);
+        for (int q = 0; q < 4; ++q) wl[k % NWL][q] = *reinterpret_cast<const f16x8_t *>(w_lds + k * 4096 + q * 1024);
     };
-    // the three bf16 planes of h for one k-step, read one group of items ahead
-    bf16x8_t hb[2][3];
-    auto read_h = [&](bf16x8_t (&dst)[3], int buf, int ks) {
+    // the two fp16 terms of h for one k-step, read one item ahead
+    f16x8_t hb[2][2];
+    auto read_h = [&](f16x8_t (&dst)[2], int buf, int ks) {
 #pragma unroll
-        for (int p = 0; p < 3; ++p)
-            dst[p] = *reinterpret_cast<const bf16x8_t *>(h_rd + (size_t)(buf * 3 + p) * 16 * HP + ks * 32);
+        for (int p = 0; p < 2; ++p)
+            dst[p] = *reinterpret_cast<const f16x8_t *>(h_rd + (size_t)(buf * 2 + p) * 16 * HP + ks * 32);
     };
 
 #pragma unroll
@@ -346,10 +395,10 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
             float hv[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float ig = sigmoid_hw(acc[0][r] + xin[0][r]);
-                const float fg = sigmoid_hw(acc[1][r] + xin[1][r]);
-                const float gg = tanh_hw(acc[2][r] + xin[2][r]);
-                const float og = sigmoid_hw(acc[3][r] + xin[3][r]);
+                const float ig = sigmoid_hw(fmaf(acc[0][r], inv_scale, xin[0][r]));
+                const float fg = sigmoid_hw(fmaf(acc[1][r], inv_scale, xin[1][r]));
+                const float gg = tanh_hw(fmaf(acc[2][r], inv_scale, xin[2][r]));
+                const float og = sigmoid_hw(fmaf(acc[3][r], inv_scale, xin[3][r]));
                 const float cn = fmaf(fg, c_reg[ut][r], ig * gg);
                 c_reg[ut][r] = cn;
                 float hn = og * tanh_hw(cn);
@@ -377,12 +426,12 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
             if constexpr (i + 1 < ITEMS) read_h(hb[(i + 1) & 1], cur, G::ks_of(i + 1));
             if constexpr (R::cls((i + 1) % ITEMS) == 0) read_wl(std::integral_constant<int, R::idx((i + 1) % ITEMS)>{});
             if constexpr (c == 2) load_w(std::integral_constant<int, (k + PF) % NS>{});
-            auto chain = [&](const bf16x8_t (&wf)[4]) {
+            auto chain = [&](const f16x8_t (&wf)[4]) {
 #pragma unroll
-                for (int p = 2; p >= 0; --p)
+                for (int p = 1; p >= 0; --p)          // the small term first
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q], hb[i & 1][p], acc[q], 0, 0, 0);
+                        acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[q], hb[i & 1][p], acc[q], 0, 0, 0);
             };
             if constexpr (c == 0) chain(wl[k % NWL]);
             else if constexpr (c == 1) chain(wres[k]);
@@ -433,8 +482,11 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
     }
     {
         const size_t frags = (size_t)a.L * 4 * DG * DG / 8;
+        hipLaunchKernelGGL(lstm_whh_scale_kernel, dim3((unsigned)a.L), dim3(1024), 0, st,
+                           static_cast<const bf16_t *>(a.W_hh), (size_t)4 * DG * DG, a.whh_scale);
         hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
-                           static_cast<const bf16_t *>(a.W_hh), const_cast<bf16x8_t *>(a.whh_packed), a.L);
+                           static_cast<const bf16_t *>(a.W_hh),
+                           reinterpret_cast<f16x8_t *>(const_cast<bf16x8_t *>(a.whh_packed)), a.whh_scale, a.L);
         const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
         if (a.d == 64)
             hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 64>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
