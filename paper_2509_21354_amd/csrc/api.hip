@@ -138,7 +138,7 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
 // W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch.
 static size_t lstm_ws_pack(const kvev_shape *sh)
 {
-    // packed W_hh and W_ih (2 bytes per element), then two floats per layer (scale of W_hh), padded to 256 bytes
+    // packed W_hh and W_ih (2 bytes per element), then a word per layer (max |W_hh|), padded to 256 bytes
     return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 +
                                      ((size_t)sh->L * 8 + 255) / 256 * 256
                                : 0;
@@ -228,7 +228,7 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         a.tb = (int)tb;
         a.whh_packed = static_cast<const bf16x8_t *>(ws);
         a.wih_packed = a.whh_packed + (size_t)sh->L * 4 * sh->d_g * sh->d_g / 8;
-        a.whh_scale = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) +
+        a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) +
                                                 (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);

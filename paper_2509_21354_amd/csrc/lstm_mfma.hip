@@ -192,15 +192,26 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
     }
 }
 
-// Per layer: the power of two s that lifts max |W_hh| into [2^14, 2^15) and its
-// inverse, scale[2l] = s, scale[2l+1] = 1/s (s = 1 for an all-zero matrix).
-__global__ __launch_bounds__(1024) void lstm_whh_scale_kernel(const bf16_t *W_hh, size_t per_layer, float *scale)
+// The power of two s that lifts max |W_hh| of a layer into [2^14, 2^15), from the
+// bit pattern of that maximum (s = 1 for an all-zero matrix).
+__device__ __forceinline__ int whh_scale_exp(uint32_t max_bits)
 {
-    __shared__ float s_max[16];
-    const int l = blockIdx.x, t = threadIdx.x;
+    const float m = __uint_as_float(max_bits);
+    int k = m > 0.f ? 14 - ilogbf(m) : 0;
+    return k > 100 ? 100 : k < -100 ? -100 : k;
+}
+
+// Per layer: the largest finite |W_hh| as a bit pattern (non-negative floats order like unsigned
+// integers, so an integer atomic max is exact and order-independent).  kScaleBlocks workgroups per
+// layer; the slots are zeroed by the W_ih re-layout kernel that runs before.
+constexpr int kScaleBlocks = 32;
+__global__ __launch_bounds__(256) void lstm_whh_max_kernel(const bf16_t *W_hh, size_t per_layer, uint32_t *max_bits)
+{
+    __shared__ float s_max[4];
+    const int l = blockIdx.x / kScaleBlocks, part = blockIdx.x % kScaleBlocks, t = threadIdx.x;
     const bf16_t *W = W_hh + (size_t)l * per_layer;
     float m = 0.f;
-    for (size_t i = (size_t)t * 8; i < per_layer; i += 1024 * 8) {
+    for (size_t i = ((size_t)part * 256 + t) * 8; i < per_layer; i += (size_t)kScaleBlocks * 256 * 8) {
         const uint4 v = *reinterpret_cast<const uint4 *>(W + i);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -215,12 +226,8 @@ __global__ __launch_bounds__(1024) void lstm_whh_scale_kernel(const bf16_t *W_hh
     if ((t & 63) == 0) s_max[t >> 6] = m;
     __syncthreads();
     if (t == 0) {
-        for (int w = 1; w < 16; ++w) m = fmaxf(m, s_max[w]);
-        int k = 0;
-        if (m > 0.f) k = 14 - ilogbf(m);
-        k = k > 100 ? 100 : k < -100 ? -100 : k;
-        scale[2 * l] = ldexpf(1.f, k);
-        scale[2 * l + 1] = ldexpf(1.f, -k);
+        m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+        atomicMax(max_bits + l, __float_as_uint(m));
     }
 }
 
@@ -229,7 +236,7 @@ __global__ __launch_bounds__(1024) void lstm_whh_scale_kernel(const bf16_t *W_hh
 // matrix would give 16 half-used cache lines per load):
 // [layer][wave][item][gate][lane][8], items in the order the wave walks them.
 template <int DG>
-__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, f16x8_t *packed, const float *scale, int L)
+__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, f16x8_t *packed, const uint32_t *max_bits, int L)
 {
     using G = Geo<DG>;
     constexpr int NW = G::NW, UT = G::UT;
@@ -247,7 +254,7 @@ __global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, 
     const bf16_t *src = W_hh + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * DG + ks * 32 + g4 * 8;
     const uint4 v = *reinterpret_cast<const uint4 *>(src);
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    const float sc = scale[2 * l];
+    const float sc = ldexpf(1.f, whh_scale_exp(max_bits[l]));
     f16x8_t o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -259,8 +266,11 @@ __global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, 
 
 // W_ih in A-fragment order for the input projection: [layer][wave][unit tile][gate][k-step][lane][8].
 template <int DG, int D>
-__global__ __launch_bounds__(256) void lstm_pack_wih_kernel(const bf16_t *W_ih, bf16x8_t *packed, int L)
+__global__ __launch_bounds__(256) void lstm_pack_wih_kernel(const bf16_t *W_ih, bf16x8_t *packed, int L, uint32_t *whh_max_bits)
 {
+    // (first job of the call: clear the per-layer maxima that the next kernel accumulates)
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < L; i += 256) whh_max_bits[i] = 0u;
     constexpr int NW = Geo<DG>::NW, UT = Geo<DG>::UT, KS = 2 * D / 32;
     const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t total = (size_t)L * NW * UT * 4 * KS * 64;
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 
     const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
     const float b_s = bf16_to_f32(static_cast<const bf16_t *>(a.b_s)[l]);
-    const float inv_scale = a.whh_scale[2 * l + 1];      // undoes the power-of-two scaling of the packed W_hh
+    const float inv_scale = ldexpf(1.f, -whh_scale_exp(a.whh_max_bits[l]));   // undoes the power-of-two scaling of the packed W_hh
 
     // state of (sequence n, units 16*UT*wave + 16*ut + 4*g4 + r) lives in this lane
     float c_reg[UT][4], h_reg[UT][4], ws_reg[UT][4];
@@ -482,18 +492,18 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
     }
     {
         const size_t frags = (size_t)a.L * 4 * DG * DG / 8;
-        hipLaunchKernelGGL(lstm_whh_scale_kernel, dim3((unsigned)a.L), dim3(1024), 0, st,
-                           static_cast<const bf16_t *>(a.W_hh), (size_t)4 * DG * DG, a.whh_scale);
-        hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
-                           static_cast<const bf16_t *>(a.W_hh),
-                           reinterpret_cast<f16x8_t *>(const_cast<bf16x8_t *>(a.whh_packed)), a.whh_scale, a.L);
         const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
         if (a.d == 64)
             hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 64>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
-                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L);
+                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L, a.whh_max_bits);
         else
             hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 128>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
-                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L);
+                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L, a.whh_max_bits);
+        hipLaunchKernelGGL(lstm_whh_max_kernel, dim3((unsigned)a.L * kScaleBlocks), dim3(256), 0, st,
+                           static_cast<const bf16_t *>(a.W_hh), (size_t)4 * DG * DG, a.whh_max_bits);
+        hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const bf16_t *>(a.W_hh),
+                           reinterpret_cast<f16x8_t *>(const_cast<bf16x8_t *>(a.whh_packed)), a.whh_max_bits, a.L);
     }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
