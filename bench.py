@@ -354,6 +354,49 @@ def main():
                              "note": "per-layer estimate incl. projections and FFN (Eq. 7); the measured speed-ups "
                                      "in `dense` are for the attention over the cache alone"}
 
+    # ---- streaming (config 4: a frame of 256 tokens arrives, the 8 chunks it completes are pooled and scored
+    # with the carried gate state, the kept set is re-selected, 8 action tokens are decoded; section 3.3 trigger) ----
+    if not args.no_extra and not args.only and args.workload == "cfg2":
+        c4 = synth.CONFIGS[4]
+        free, _ = torch.cuda.mem_get_info()
+        if free > 12 << 30:
+            kv4 = synth.make_qkv(c4, dev)
+            w4 = synth.make_weights(c4, dev)
+            s4 = kb.DecodeState(c4)
+            q4 = synth.make_stream_queries(c4, dev)
+            O4 = torch.empty_like(kv4["Q"])
+            wK4, wV4, lw4 = kb.mlp_weights(w4, "K"), kb.mlp_weights(w4, "V"), kb.lstm_weights(w4)
+            sh4 = s4.shape
+
+            def frame(si, done):
+                sh4.T = (si + 1) * c4.frame
+                n4 = sh4.T // c4.C
+                kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
+                kb.kvev_lstm_gate(sh4, s4.Kbar, s4.Vbar, lw4, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
+                kb.kvev_select(sh4, s4.util, s4.gate, kb.SELECT_TOPK, c4.k, 0.0, s4.k_cap, s4.idx, s4.count)
+                for j in range(c4.decode_per_step):
+                    kb.kvev_gated_attention(sh4, q4[si, j], 1, kv4["K"], kv4["V"], s4.Kbar, s4.Vbar, s4.idx, s4.count,
+                                            s4.k_cap, O4, s4.ws)
+                return n4
+            for rep in range(2):                      # first pass warms up, second is timed
+                s4.h.zero_(); s4.c.zero_()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                done = 0
+                for si in range(c4.steps):
+                    done = frame(si, done)
+                e1.record()
+                torch.cuda.synchronize()
+            t_frame = e0.elapsed_time(e1) * 1e3 / c4.steps
+            out["streaming_cfg4"] = {
+                "workload": c4.name + f" ({c4.steps} frames of {c4.frame} tokens, {c4.decode_per_step} decoded tokens per frame, "
+                                      f"cache grows to {c4.T} tokens)",
+                "us_per_frame": round(t_frame, 2),
+                "decoded_tokens_per_s_per_layer": round(c4.B * c4.decode_per_step / (t_frame * 1e-6), 1),
+                "frames_per_s": round(1e6 / t_frame, 1)}
+            del kv4, s4, q4, O4
+
     # ---- large launch: config 3 attention, layer-batched (the bandwidth-bound regime) ----
     if not args.no_extra and not args.only and args.workload == "cfg2":
         del sets
