@@ -136,6 +136,12 @@ template <typename V> __device__ __forceinline__ V buffer_load16(__amdgpu_buffer
     const u32x4_t raw = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, (int)soff, 0);
     return __builtin_bit_cast(V, raw);
 }
+// The same with the non-temporal hint: for data read once, so that it does not push re-used lines out of L2.
+template <typename V> __device__ __forceinline__ V buffer_load16_nt(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff)
+{
+    const u32x4_t raw = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, (int)soff, 2);
+    return __builtin_bit_cast(V, raw);
+}
 
 // sum over the 16 lanes of a lane group (lanes that share lane/16)
 __device__ __forceinline__ float group16_sum(float v)

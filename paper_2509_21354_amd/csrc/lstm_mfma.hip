@@ -54,7 +54,7 @@ __device__ __forceinline__ float tanh_hw(float x)
     return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
 }
 
-constexpr int kTT = 4;   // steps per wave pass of the input projection
+constexpr int kTT = 8;   // steps per workgroup of the input projection
 
 // Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
 // contiguous run of sequence groups, i.e. a few layers at a time, so that the
@@ -136,57 +136,68 @@ __device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, 
     return ((((size_t)group * tb + tt) * Geo<DG>::NW + wave) * Geo<DG>::UT + ut) * 4 + q;
 }
 
+// The 16 sequences x kTT steps of input rows [Kbar_t ; Vbar_t] that a workgroup projects are staged once in
+// LDS (every wave needs all of them as the B operand); a wave keeps the 2d-long weight rows of one (unit tile,
+// gate) in registers and walks the kTT steps with them.  Its output is the bulk of the traffic (4*d_g floats per
+// sequence and step), written as 1 KiB per wave-level store in the fragment layout the recurrence reads back.
 template <int DG, int D>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb)
 {
-    constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT, XP = 2 * D + 8, THREADS = Geo<DG>::THREADS;
+    extern __shared__ __align__(16) unsigned char smem_in[];
+    bf16_t *s_x = reinterpret_cast<bf16_t *>(smem_in);           // [kTT][16][XP]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g4 = lane >> 4;
     const int gpl = (a.BH + 15) / 16;
     const int gid = xcd_order(blockIdx.x, gridDim.x);
     const int l = gid / gpl, grp = gid % gpl;
-    const int sl = min(grp * 16 + n, a.BH - 1);
-    const size_t s = (size_t)l * a.BH + sl;
     const int tt0 = blockIdx.y * kTT;
 
+    // stage the rows: 16-byte pieces, 2D/8 per row (the first D/8 from Kbar, the rest from Vbar)
     const bf16_t *Kbar = static_cast<const bf16_t *>(a.Kbar), *Vbar = static_cast<const bf16_t *>(a.Vbar);
-    bf16x8_t xb[kTT][KS];
-#pragma unroll
-    for (int j = 0; j < kTT; ++j) {
+    constexpr int PPR = 2 * D / 8;
+    for (int p = tid; p < kTT * 16 * PPR; p += THREADS) {
+        const int piece = p % PPR, row = p / PPR, sq = row % 16, j = row / 16;
+        const size_t s = (size_t)l * a.BH + min(grp * 16 + sq, a.BH - 1);
         const int t = t0 + min(tt0 + j, nb - 1);
-        const size_t row = (s * a.N_cap + t) * D;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int e = ks * 32 + g4 * 8;
-            const bf16_t *src = e < D ? Kbar + row + e : Vbar + row + (e - D);
-            xb[j][ks] = *reinterpret_cast<const bf16x8_t *>(src);
-        }
+        const int e = piece * 8;
+        const bf16_t *src = e < D ? Kbar + (s * a.N_cap + t) * D + e : Vbar + (s * a.N_cap + t) * D + (e - D);
+        *reinterpret_cast<bf16x8_t *>(s_x + (size_t)row * XP + e) = *reinterpret_cast<const bf16x8_t *>(src);
     }
+    __syncthreads();
+
     const bf16x8_t *Wp = a.wih_packed + ((size_t)l * Geo<DG>::NW + wave) * UT * 4 * KS * 64 + lane;
     const bf16_t *b_ih = static_cast<const bf16_t *>(a.b_ih) + (size_t)l * 4 * DG;
     const bf16_t *b_hh = static_cast<const bf16_t *>(a.b_hh) + (size_t)l * 4 * DG;
-    for (int ut = 0; ut < UT; ++ut) {
+    const bf16_t *xrd = s_x + (size_t)n * XP + g4 * 8;           // + j*16*XP + ks*32
+    bf16x8_t wf[2][KS];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row0 = q * DG + wave * 16 * UT + ut * 16;
-            bf16x8_t wf[KS];
+    for (int ks = 0; ks < KS; ++ks) wf[0][ks] = Wp[(size_t)ks * 64];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) wf[ks] = Wp[(((size_t)ut * 4 + q) * KS + ks) * 64];
-            float bias[4];
+    for (int it = 0; it < UT * 4; ++it) {
+        const int ut = it / 4, q = it % 4;
+        const int row0 = q * DG + wave * 16 * UT + ut * 16;
+        // the next (unit tile, gate)'s weight rows travel while this one is used
+        if (it + 1 < UT * 4) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                bias[r] = bf16_to_f32(b_ih[row0 + 4 * g4 + r]) + bf16_to_f32(b_hh[row0 + 4 * g4 + r]);
+            for (int ks = 0; ks < KS; ++ks) wf[(it + 1) & 1][ks] = Wp[((size_t)(it + 1) * KS + ks) * 64];
+        }
+        float bias[4];
 #pragma unroll
-            for (int j = 0; j < kTT; ++j) {
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 4; ++r)
+            bias[r] = bf16_to_f32(b_ih[row0 + 4 * g4 + r]) + bf16_to_f32(b_hh[row0 + 4 * g4 + r]);
+#pragma unroll 2
+        for (int j = 0; j < kTT; ++j) {           // (not fully unrolled: the rows' fragments would fill the register file)
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], xb[j][ks], acc, 0, 0, 0);
-                if (tt0 + j < nb) {
-                    float4 o = make_float4(acc[0] + bias[0], acc[1] + bias[1], acc[2] + bias[2], acc[3] + bias[3]);
-                    float *dst = a.xproj + xp_block<DG>(gid, a.tb, tt0 + j, wave, ut, q) * 256 + lane * 4;
-                    *reinterpret_cast<float4 *>(dst) = o;
-                }
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8_t xb = *reinterpret_cast<const bf16x8_t *>(xrd + (size_t)j * 16 * XP + ks * 32);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[it & 1][ks], xb, acc, 0, 0, 0);
+            }
+            if (tt0 + j < nb) {
+                const f32x4_t o = {acc[0] + bias[0], acc[1] + bias[1], acc[2] + bias[2], acc[3] + bias[3]};
+                float *dst = a.xproj + xp_block<DG>(gid, a.tb, tt0 + j, wave, ut, q) * 256 + lane * 4;
+                *reinterpret_cast<f32x4_t *>(dst) = o;
             }
         }
     }
@@ -428,7 +439,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
             if constexpr (ks == 0) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    xin[q] = buffer_load16<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)(tt * NW * UT + ut) * 4096);
+                    xin[q] = buffer_load16_nt<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)(tt * NW * UT + ut) * 4096);
                     acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 }
             }
@@ -488,6 +499,10 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_kernel<DG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
+        // (the in-projection's staged rows pass 64 KiB at d = 128)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
+        if (e != hipSuccess) return e;
         attr_set = true;
     }
     {
@@ -509,9 +524,9 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
         const dim3 grid_in(groups, (unsigned)((nb + kTT - 1) / kTT));
         if (a.d == 64)
-            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64>), grid_in, dim3(Geo<DG>::THREADS), 0, st, a, t0, nb);
+            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64>), grid_in, dim3(Geo<DG>::THREADS), (size_t)kTT * 16 * (2 * 64 + 8) * sizeof(bf16_t), st, a, t0, nb);
         else
-            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128>), grid_in, dim3(Geo<DG>::THREADS), 0, st, a, t0, nb);
+            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128>), grid_in, dim3(Geo<DG>::THREADS), (size_t)kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t), st, a, t0, nb);
         hipLaunchKernelGGL((lstm_rec_kernel<DG>), dim3(groups), dim3(Geo<DG>::THREADS), lds, st, a, t0, nb);
     }
     return hipGetLastError();
