@@ -37,7 +37,7 @@
 
 enum { KVO_F32 = 0, KVO_BF16 = 1 };
 enum { KVO_OK = 0, KVO_BAD_ARG = 1 };
-enum { KVO_POOL_MEAN = 0, KVO_POOL_MLP = 1, KVO_POOL_MAX = 2 };
+enum { KVO_POOL_MEAN = 0, KVO_POOL_MLP = 1, KVO_POOL_MAX = 2, KVO_POOL_TOKEN_MLP = 3 };
 
 /* ---------- storage <-> double ------------------------------------------- */
 
@@ -100,7 +100,11 @@ double kvo_gelu(double x) { return gelu(x); }
  * its arithmetic mean; MLP_K and MLP_V have separate weights; weights are per
  * layer, shared by batch rows and heads.  Mode MEAN stops after the mean;
  * mode MAX (one of the alternative aggregators section 3 names, "pooling")
- * takes the element-wise maximum of the chunk instead, no weights.
+ * takes the element-wise maximum of the chunk instead, no weights.  Mode
+ * TOKEN_MLP is the other way a set can enter an MLP of width d: the same
+ * d -> d_sum -> d MLP is applied to every token of the chunk and the C outputs
+ * are averaged (the "multi-layer perceptron" aggregator of section 3 read as a
+ * per-element network followed by a symmetric reduction).
  *   K, V        [L,B,H,T_cap,d]       Kbar, Vbar [L,B,H,N_cap,d]
  *   W1 [L,d_sum,d] b1 [L,d_sum] W2 [L,d,d_sum] b2 [L,d]     (row-major out x in)
  * Writes summary rows [c0, c1); needs 0 <= c0 <= c1 <= floor(T/C) <= N_cap.
@@ -120,6 +124,27 @@ static void pool_one(int dtype, int d, int C, int d_sum, int mode,
             }
             st(Y, dtype, y_off + e, m);
         }
+        return;
+    }
+    if (mode == KVO_POOL_TOKEN_MLP) {       /* y = (1/C) sum_j MLP(x_j); mean[] holds the running sum of outputs */
+        for (int e = 0; e < d; ++e)
+            mean[e] = 0.0;
+        for (int j = 0; j < C; ++j) {
+            for (int u = 0; u < d_sum; ++u) {
+                double z = ld(b1, dtype, b1_off + u);
+                for (int e = 0; e < d; ++e)
+                    z += ld(W1, dtype, w1_off + (size_t)u * d + e) * ld(X, dtype, x_off + (size_t)j * d + e);
+                act[u] = gelu(z);
+            }
+            for (int e = 0; e < d; ++e) {
+                double y = ld(b2, dtype, b2_off + e);
+                for (int u = 0; u < d_sum; ++u)
+                    y += ld(W2, dtype, w2_off + (size_t)e * d_sum + u) * act[u];
+                mean[e] += y;
+            }
+        }
+        for (int e = 0; e < d; ++e)
+            st(Y, dtype, y_off + e, mean[e] / (double)C);
         return;
     }
     for (int e = 0; e < d; ++e) {
@@ -156,6 +181,8 @@ int kvo_chunk_pool(int dtype, int L, int B, int H, int d, int T, int T_cap, int 
     if (L < 1 || B < 1 || H < 1 || d < 1 || C < 1 || T < 0 || T > T_cap || d_sum < 1)
         return KVO_BAD_ARG;
     if (c0 < 0 || c0 > c1 || c1 > T / C || T / C > N_cap)
+        return KVO_BAD_ARG;
+    if (mode < KVO_POOL_MEAN || mode > KVO_POOL_TOKEN_MLP)
         return KVO_BAD_ARG;
     double *mean = malloc(sizeof(double) * (size_t)d);
     double *act = malloc(sizeof(double) * (size_t)d_sum);

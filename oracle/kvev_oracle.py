@@ -23,7 +23,7 @@ _SRC = os.path.join(_HERE, "kvev_oracle.c")
 _LIB = os.path.join(_HERE, "libkvev_oracle.so")
 
 F32, BF16 = 0, 1
-POOL_MEAN, POOL_MLP, POOL_MAX = 0, 1, 2
+POOL_MEAN, POOL_MLP, POOL_MAX, POOL_TOKEN_MLP = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> str:

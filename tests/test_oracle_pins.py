@@ -137,6 +137,49 @@ def test_pool_max_is_the_library_maximum(oracle):
     assert (one[0] == t["K"].numpy()).all()
 
 
+def test_pool_token_mlp_is_the_library_mlp_per_token_then_the_mean(oracle):
+    """Mode TOKEN_MLP (section 3's "multi-layer perceptron" aggregator read as a per-token
+    network followed by the average): against the library's linear layers and GELU applied
+    to every token, against the factored form (the second layer is linear, so it commutes
+    with the mean), and through its special cases."""
+    cfg = TINY
+    t = _inputs(cfg)
+    wK, wV = _mlp_w(t, "K"), _mlp_w(t, "V")
+    Kbar, Vbar = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_TOKEN_MLP,
+                                   wK, wV, 0, cfg.N)
+    for X, Y, kv in ((t["K"], Kbar, "K"), (t["V"], Vbar, "V")):
+        x = _f64(X).view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d)
+        for l in range(cfg.L):
+            W1, b1, W2, b2 = (_f64(w[l]) for w in _mlp_w(t, kv))
+            a = torch.nn.functional.gelu(torch.nn.functional.linear(x[l], W1, b1))     # [B,H,N,C,d_sum]
+            y = torch.nn.functional.linear(a, W2, b2).mean(dim=3)
+            assert np.abs(Y[l] - y.to(torch.float32).numpy()).max() <= 1e-6
+            y2 = torch.nn.functional.linear(a.mean(dim=3), W2, b2)                      # factored form
+            assert np.abs(Y[l] - y2.to(torch.float32).numpy()).max() <= 1e-6
+    # it is not the MLP of the mean (GELU is not linear) ...
+    ref = oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_MLP, wK, wV, 0, cfg.N)
+    assert np.abs(Kbar - ref[0]).max() > 1e-3
+    # ... except for chunks of one token, or of equal tokens
+    one_a = oracle.chunk_pool(t["K"], t["V"], cfg.T, 1, cfg.T, cfg.d_sum, oracle.POOL_TOKEN_MLP, wK, wV, 0, cfg.T)
+    one_b = oracle.chunk_pool(t["K"], t["V"], cfg.T, 1, cfg.T, cfg.d_sum, oracle.POOL_MLP, wK, wV, 0, cfg.T)
+    assert (one_a[0] == one_b[0]).all() and (one_a[1] == one_b[1]).all()
+    x = t["K"][:, :, :, :1]
+    for C in (3, 8):
+        Kc = x.expand(-1, -1, -1, C, -1).contiguous()
+        a = oracle.chunk_pool(Kc, Kc, C, C, 1, cfg.d_sum, oracle.POOL_TOKEN_MLP, wK, wK, 0, 1)
+        b = oracle.chunk_pool(x.contiguous(), x.contiguous(), 1, 1, 1, cfg.d_sum, oracle.POOL_MLP, wK, wK, 0, 1)
+        assert np.abs(a[0] - b[0]).max() < 1e-6
+    # token order inside a chunk does not matter; K and V use their own weights
+    K5 = t["K"].view(cfg.L, cfg.B, cfg.H, cfg.N, cfg.C, cfg.d)
+    Kp = K5[:, :, :, :, torch.tensor([2, 0, 3, 1])].reshape(t["K"].shape).contiguous()
+    got = oracle.chunk_pool(Kp, t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_TOKEN_MLP, wK, wV, 0, cfg.N)
+    assert np.abs(got[0] - Kbar).max() < 1e-6 and (got[1] == Vbar).all()
+    swapped = oracle.chunk_pool(t["V"], t["K"], cfg.T, cfg.C, cfg.N, cfg.d_sum, oracle.POOL_TOKEN_MLP, wV, wK, 0, cfg.N)
+    assert (swapped[0] == Vbar).all() and (swapped[1] == Kbar).all()
+    with pytest.raises(ValueError):
+        oracle.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, cfg.N, cfg.d_sum, 4, wK, wV, 0, cfg.N)
+
+
 def test_pool_bf16_storage_rounds_once(oracle):
     cfg = TINY.replace(dtype="bf16", number=91)
     t = _inputs(cfg)
