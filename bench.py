@@ -354,6 +354,29 @@ def main():
                              "note": "per-layer estimate incl. projections and FFN (Eq. 7); the measured speed-ups "
                                      "in `dense` are for the attention over the cache alone"}
 
+    # ---- the other aggregators section 3 names (mean, maximum, the MLP on every token), same inputs ----
+    if not args.only:
+        aggs = {}
+        S_kv, N_, es = cfg.L * cfg.B * cfg.kv_heads, cfg.N, cfg.elem_size
+        tokens = S_kv * N_ * cfg.C
+        for name, mode in (("mean", kb.POOL_MEAN), ("max", kb.POOL_MAX), ("mlp_of_mean", kb.POOL_MLP),
+                           ("mean_of_token_mlp", kb.POOL_TOKEN_MLP)):
+            t_a = time_alone(lambda t, m=mode: kb.kvev_chunk_pool(sh, t["K"], t["V"], m, wK, wV, 0, N_, st.Kbar, st.Vbar, st.ws),
+                             max(20, args.steps))
+            e = {"us": round(t_a, 3), "hbm_GBps": round(cost["pool"]["bytes"] / t_a / 1e3, 1)}
+            if mode == kb.POOL_TOKEN_MLP:
+                # 2*C*d*d_sum flop per chunk and side on the matrix cores, C*d_sum GELUs per chunk and side on the
+                # vector ALUs (12 operations + one quarter-rate exp2 = 15 issue slots of 4 clocks per 64 of them)
+                gelus = 2 * tokens * cfg.d_sum
+                peak = 256 * 4 * 2.4e9 * 64 / (15 * 4)
+                e.update({"layer1_TFLOPs": round(2 * tokens * 2 * cfg.d * cfg.d_sum / t_a / 1e6, 1),
+                          "G_gelu_per_s": round(gelus / t_a / 1e3, 1),
+                          "alu_bound": {"bound": "alu", "achieved": round(gelus / t_a / 1e3, 1), "peak": round(peak / 1e9, 1),
+                                        "unit": "G GELU/s", "frac": round(gelus / t_a / 1e3 / (peak / 1e9), 4)}})
+            aggs[name] = e
+        out["aggregators"] = aggs
+        pool(sets[0])          # leave the headline aggregator's summaries in place
+
     # ---- streaming (config 4: a frame of 256 tokens arrives, the 8 chunks it completes are pooled and scored
     # with the carried gate state, the kept set is re-selected, 8 action tokens are decoded; section 3.3 trigger) ----
     if not args.no_extra and not args.only and args.workload == "cfg2":

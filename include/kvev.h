@@ -39,7 +39,7 @@ extern "C" {
 enum { KVEV_OK = 0, KVEV_ERR_INVALID_ARG = 1, KVEV_ERR_UNSUPPORTED = 2, KVEV_ERR_WORKSPACE = 3,
        KVEV_ERR_HIP = 4 };
 enum { KVEV_F32 = 0, KVEV_BF16 = 1 };           /* storage type of Q/K/V, summaries, weights */
-enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1, KVEV_POOL_MAX = 2 };
+enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1, KVEV_POOL_MAX = 2, KVEV_POOL_TOKEN_MLP = 3 };
 enum { KVEV_SELECT_TOPK = 0, KVEV_SELECT_THRESHOLD = 1 };
 enum { KVEV_OP_CHUNK_POOL = 0, KVEV_OP_LSTM_GATE = 1, KVEV_OP_SELECT = 2,
        KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4, KVEV_OP_COMPACT_ATTENTION = 5 };
@@ -82,8 +82,12 @@ typedef struct { const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s; } kvev_lstm_
  * the same for V with the V weights; KVEV_POOL_MEAN stores xbar itself and
  * KVEV_POOL_MAX (the "pooling" alternative section 3 names) the element-wise
  * maximum of the chunk's C rows, exactly (wK, wV may then be NULL; inputs are
- * taken to be free of NaN).  Mean, both layers and GELU are evaluated in fp32-grade
- * arithmetic; each summary element is rounded once to the storage dtype.
+ * taken to be free of NaN).  KVEV_POOL_TOKEN_MLP applies the same MLP to every
+ * token of the chunk and averages the C outputs (section 3's multi-layer
+ * perceptron aggregator read as a per-token network under a symmetric reduction):
+ * Kbar[c] = (1/C) sum_j [ W2 * GELU(W1 * k_j + b1) + b2 ].  Mean, both layers and GELU
+ * are evaluated in fp32-grade arithmetic; each summary element is rounded once to the
+ * storage dtype.
  *   K, V        [L,B,H,T_cap,d]   read: tokens [chunk_begin*C, chunk_end*C)
  *   Kbar, Vbar  [L,B,H,N_cap,d]   written: rows [chunk_begin, chunk_end) only
  * Needs 0 <= chunk_begin <= chunk_end <= floor(T/C) <= N_cap.  Workspace: none

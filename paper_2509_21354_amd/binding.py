@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libkvev.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 F32, BF16 = 0, 1
-POOL_MEAN, POOL_MLP, POOL_MAX = 0, 1, 2
+POOL_MEAN, POOL_MLP, POOL_MAX, POOL_TOKEN_MLP = 0, 1, 2, 3
 SELECT_TOPK, SELECT_THRESHOLD = 0, 1
 OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, OP_COMPACT_ATTENTION = range(6)
 

@@ -164,11 +164,12 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     (void)ws; (void)ws_bytes;
     int rc = check_shape(sh);
     if (rc) return rc;
-    if (pool_mode != KVEV_POOL_MEAN && pool_mode != KVEV_POOL_MLP && pool_mode != KVEV_POOL_MAX) return KVEV_ERR_UNSUPPORTED;
+    if (pool_mode < KVEV_POOL_MEAN || pool_mode > KVEV_POOL_TOKEN_MLP) return KVEV_ERR_UNSUPPORTED;
+    const bool has_mlp = pool_mode == KVEV_POOL_MLP || pool_mode == KVEV_POOL_TOKEN_MLP;
     if (!K || !V || !Kbar || !Vbar || !aligned16(K) || !aligned16(V) || !aligned16(Kbar) || !aligned16(Vbar))
         return KVEV_ERR_INVALID_ARG;
     if (chunk_begin < 0 || chunk_begin > chunk_end || chunk_end > sh->T / sh->C) return KVEV_ERR_INVALID_ARG;
-    if (pool_mode == KVEV_POOL_MLP) {
+    if (has_mlp) {
         if (!wK || !wV) return KVEV_ERR_INVALID_ARG;
         const void *ptrs[8] = {wK->W1, wK->b1, wK->W2, wK->b2, wV->W1, wV->b1, wV->W2, wV->b2};
         for (const void *p : ptrs)
@@ -182,7 +183,7 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     PoolArgs a;
     memset(&a, 0, sizeof a);
     a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar;
-    if (pool_mode == KVEV_POOL_MLP) {
+    if (has_mlp) {
         a.W1K = wK->W1; a.b1K = wK->b1; a.W2K = wK->W2; a.b2K = wK->b2;
         a.W1V = wV->W1; a.b1V = wV->b1; a.W2V = wV->W2; a.b2V = wV->b2;
     }
@@ -190,8 +191,12 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
     // bf16 storage with a hidden width the 16x16x32 tiling divides goes to the matrix cores
     const bool mfma = sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
-    hipError_t e = mfma ? launch_pool_mfma(a, static_cast<hipStream_t>(stream))
-                        : launch_pool_generic(a, sh->dtype, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (pool_mode == KVEV_POOL_TOKEN_MLP && mfma && sh->d_sum <= 256 && pool_token_mfma_lds(sh->d, sh->d_sum) <= 160 * 1024)
+        e = launch_pool_token_mfma(a, static_cast<hipStream_t>(stream));     // W1 of both sides fits in LDS
+    else
+        e = mfma && pool_mode != KVEV_POOL_TOKEN_MLP ? launch_pool_mfma(a, static_cast<hipStream_t>(stream))
+                                                     : launch_pool_generic(a, sh->dtype, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 

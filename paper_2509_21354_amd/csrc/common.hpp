@@ -143,6 +143,17 @@ template <typename V> __device__ __forceinline__ V buffer_load16_nt(__amdgpu_buf
     return __builtin_bit_cast(V, raw);
 }
 
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // sum over the 16 lanes of a lane group (lanes that share lane/16)
 __device__ __forceinline__ float group16_sum(float v)
 {

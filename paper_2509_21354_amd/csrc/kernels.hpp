@@ -67,6 +67,8 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t st);
 hipError_t launch_retain(const RetainArgs &a, hipStream_t st);
 hipError_t launch_pool_generic(const PoolArgs &a, int dtype, hipStream_t st);
 hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st);          // bf16
+hipError_t launch_pool_token_mfma(const PoolArgs &a, hipStream_t st);    // bf16, the MLP on every token
+size_t pool_token_mfma_lds(int d, int d_sum);                            // its LDS need in bytes
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
 

@@ -117,17 +117,6 @@ template <int DG> struct Res {
     static_assert(lds <= 160 * 1024, "LDS budget of a CU");
 };
 
-template <class F, int... Is>
-__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
-template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // Scratch layout: 1 KiB blocks of 64 lanes x 4 floats, one per
 // (sequence group, step of the block, wave, unit tile, gate).
 template <int DG>

@@ -27,6 +27,31 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a)
     const T *Kp = static_cast<const T *>(a.K) + ((size_t)s * a.T_cap + (size_t)c * a.C) * D;
     const T *Vp = static_cast<const T *>(a.V) + ((size_t)s * a.T_cap + (size_t)c * a.C) * D;
     const bool is_max = a.mode == KVEV_POOL_MAX;     // element-wise maximum instead of the mean
+    T *Kb = static_cast<T *>(a.Kbar) + ((size_t)s * a.N_cap + c) * D;
+    T *Vb = static_cast<T *>(a.Vbar) + ((size_t)s * a.N_cap + c) * D;
+    const int ds = a.d_sum;
+    if (a.mode == KVEV_POOL_TOKEN_MLP) {
+        // the MLP on every token, outputs averaged; layer 2 is linear, so the average is taken over the
+        // hidden activations: a 16-lane group keeps one W1 row in registers and walks the chunk's tokens
+        for (int o = grp; o < 2 * ds; o += 16) {
+            const int kv = o / ds, u = o % ds;
+            const T *W1 = static_cast<const T *>(kv ? a.W1V : a.W1K) + ((size_t)l * ds + u) * D;
+            const float b1 = Storage<T>::load(static_cast<const T *>(kv ? a.b1V : a.b1K) + (size_t)l * ds + u);
+            float w[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) w[e] = Storage<T>::load(W1 + cl + 16 * e);
+            const T *X = kv ? Vp : Kp;
+            float total = 0.f;
+            for (int j = 0; j < a.C; ++j) {
+                float acc = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc = fmaf(w[e], Storage<T>::load(X + (size_t)j * D + cl + 16 * e), acc);
+                total += gelu_erf(group16_sum(acc) + b1);
+            }
+            if (cl == 0) act[kv * ds + u] = total / (float)a.C;
+        }
+        __syncthreads();
+    } else {
     float ak[EPL], av[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) ak[e] = av[e] = is_max ? -INFINITY : 0.f;
@@ -55,14 +80,11 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a)
     }
     __syncthreads();
 
-    T *Kb = static_cast<T *>(a.Kbar) + ((size_t)s * a.N_cap + c) * D;
-    T *Vb = static_cast<T *>(a.Vbar) + ((size_t)s * a.N_cap + c) * D;
     if (a.mode != KVEV_POOL_MLP) {
         for (int i = tid; i < 2 * D; i += 256) Storage<T>::store((i < D ? Kb : Vb) + (i % D), mean[i]);
         return;
     }
 
-    const int ds = a.d_sum;
     // layer 1: 2*d_sum dot products of length D, one per 16-lane group at a time
     for (int o = grp; o < 2 * ds; o += 16) {
         const int kv = o / ds, u = o % ds;
@@ -76,6 +98,7 @@ __global__ __launch_bounds__(256) void pool_generic_kernel(PoolArgs a)
         }
     }
     __syncthreads();
+    }
     // layer 2: 2*D dot products of length d_sum
     for (int o = grp; o < 2 * D; o += 16) {
         const int kv = o / D, e = o % D;

@@ -75,6 +75,9 @@ def test_pointer_range_and_mode_validation():
     assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, wr, wr, 0, 129, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MLP, wr, wr, -1, 4, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_MEAN, None, None, 7, 7, FAKE, FAKE, None, 0, None) == kb.OK  # empty range
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_TOKEN_MLP, wr, None, 0, 1, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG  # needs both weight sets
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, kb.POOL_TOKEN_MLP, wr, wr, 7, 7, FAKE, FAKE, None, 0, None) == kb.OK
+    assert L.kvev_chunk_pool(r, FAKE, FAKE, -1, wr, wr, 0, 1, FAKE, FAKE, None, 0, None) == kb.ERR_UNSUPPORTED
     # a trailing partial chunk is not poolable
     sh2 = _shape(T=4095)
     assert L.kvev_chunk_pool(ctypes.byref(sh2), FAKE, FAKE, kb.POOL_MEAN, None, None, 0, 128, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG

@@ -158,11 +158,15 @@ POOL_CASES = [
     _cfg(134, "bf16", d=64, T=600, C=24, d_sum=64),
     _cfg(135, "bf16", d=128, T=512, C=64, d_sum=48),          # d_sum the MFMA tiling does not take
     _cfg(136, "bf16", d=128, T=40, C=1, d_sum=128, L=1),
+    _cfg(137, "bf16", d=64, T=200, C=40, d_sum=256, L=1, B=1, H=3),     # widest hidden layer the per-token kernel holds in LDS
+    _cfg(138, "bf16", d=128, T=96, C=16, d_sum=256, L=1, B=1, H=2),     # ... and one it does not (generic kernel for that mode)
+    _cfg(139, "bf16", d=128, T=200, C=48, d_sum=192, L=2, B=1, H=9),    # its widest at d = 128; 9 rows per layer: ragged tile
 ]
 
 
 @pytest.mark.parametrize("cfg", POOL_CASES, ids=lambda c: c.name)
-@pytest.mark.parametrize("mode", [kb.POOL_MLP, kb.POOL_MEAN, kb.POOL_MAX], ids=["mlp", "mean", "max"])
+@pytest.mark.parametrize("mode", [kb.POOL_MLP, kb.POOL_MEAN, kb.POOL_MAX, kb.POOL_TOKEN_MLP],
+                         ids=["mlp", "mean", "max", "token_mlp"])
 def test_chunk_pool(cfg, mode):
     t = synth.make_inputs(cfg, "cpu")
     g = dev(t)
