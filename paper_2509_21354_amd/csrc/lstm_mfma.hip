@@ -54,7 +54,7 @@ __device__ __forceinline__ float tanh_hw(float x)
     return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
 }
 
-constexpr int kTT = 8;   // steps per workgroup of the input projection
+constexpr int kTT = 8;   // steps per workgroup of the input projection (2 when that leaves compute units idle)
 
 // Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
 // contiguous run of sequence groups, i.e. a few layers at a time, so that the
@@ -125,27 +125,27 @@ __device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, 
     return ((((size_t)group * tb + tt) * Geo<DG>::NW + wave) * Geo<DG>::UT + ut) * 4 + q;
 }
 
-// The 16 sequences x kTT steps of input rows [Kbar_t ; Vbar_t] that a workgroup projects are staged once in
+// The 16 sequences x TT steps of input rows [Kbar_t ; Vbar_t] that a workgroup projects are staged once in
 // LDS (every wave needs all of them as the B operand); a wave keeps the 2d-long weight rows of one (unit tile,
-// gate) in registers and walks the kTT steps with them.  Its output is the bulk of the traffic (4*d_g floats per
+// gate) in registers and walks the TT steps with them.  Its output is the bulk of the traffic (4*d_g floats per
 // sequence and step), written as 1 KiB per wave-level store in the fragment layout the recurrence reads back.
-template <int DG, int D>
+template <int DG, int D, int TT>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb)
 {
     constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT, XP = 2 * D + 8, THREADS = Geo<DG>::THREADS;
     extern __shared__ __align__(16) unsigned char smem_in[];
-    bf16_t *s_x = reinterpret_cast<bf16_t *>(smem_in);           // [kTT][16][XP]
+    bf16_t *s_x = reinterpret_cast<bf16_t *>(smem_in);           // [TT][16][XP]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g4 = lane >> 4;
     const int gpl = (a.BH + 15) / 16;
     const int gid = xcd_order(blockIdx.x, gridDim.x);
     const int l = gid / gpl, grp = gid % gpl;
-    const int tt0 = blockIdx.y * kTT;
+    const int tt0 = blockIdx.y * TT;
 
     // stage the rows: 16-byte pieces, 2D/8 per row (the first D/8 from Kbar, the rest from Vbar)
     const bf16_t *Kbar = static_cast<const bf16_t *>(a.Kbar), *Vbar = static_cast<const bf16_t *>(a.Vbar);
     constexpr int PPR = 2 * D / 8;
-    for (int p = tid; p < kTT * 16 * PPR; p += THREADS) {
+    for (int p = tid; p < TT * 16 * PPR; p += THREADS) {
         const int piece = p % PPR, row = p / PPR, sq = row % 16, j = row / 16;
         const size_t s = (size_t)l * a.BH + min(grp * 16 + sq, a.BH - 1);
         const int t = t0 + min(tt0 + j, nb - 1);
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
         for (int r = 0; r < 4; ++r)
             bias[r] = bf16_to_f32(b_ih[row0 + 4 * g4 + r]) + bf16_to_f32(b_hh[row0 + 4 * g4 + r]);
 #pragma unroll 2
-        for (int j = 0; j < kTT; ++j) {           // (not fully unrolled: the rows' fragments would fill the register file)
+        for (int j = 0; j < TT; ++j) {           // (not fully unrolled: the rows' fragments would fill the register file)
             f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -489,7 +489,7 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         // (the in-projection's staged rows pass 64 KiB at d = 128)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128, kTT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -511,11 +511,18 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
     }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
-        const dim3 grid_in(groups, (unsigned)((nb + kTT - 1) / kTT));
-        if (a.d == 64)
-            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64>), grid_in, dim3(Geo<DG>::THREADS), (size_t)kTT * 16 * (2 * 64 + 8) * sizeof(bf16_t), st, a, t0, nb);
-        else
-            hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128>), grid_in, dim3(Geo<DG>::THREADS), (size_t)kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t), st, a, t0, nb);
+        // few sequences: shorter runs of steps per workgroup so that the launch still covers the chip
+        const bool small = (size_t)groups * ((nb + kTT - 1) / kTT) < 256;
+        const int tt = small ? 2 : kTT;
+        const dim3 grid_in(groups, (unsigned)((nb + tt - 1) / tt));
+        const size_t lds_in = (size_t)tt * 16 * (2 * a.d + 8) * sizeof(bf16_t);
+        if (a.d == 64) {
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+        } else {
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+        }
         hipLaunchKernelGGL((lstm_rec_kernel<DG>), dim3(groups), dim3(Geo<DG>::THREADS), lds, st, a, t0, nb);
     }
     return hipGetLastError();
