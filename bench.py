@@ -267,6 +267,48 @@ def main():
         except Exception as ex:  # graph capture is a reporting extra: never fail the bench on it
             out["steady_state"]["graph_replay_error"] = str(ex)[:200]
 
+    # ---- the whole cold step replayed from a HIP graph (R steps, one per input set, captured once): the same
+    # kernels without the host launch path between them; every replay is checked against the eager result ----
+    if not args.only:
+        try:
+            for n, f in stages:
+                f(sets[0])
+            torch.cuda.synchronize()
+            ref_O, ref_idx = O.clone(), st.idx.clone()
+            grc = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for n, f in stages:
+                    f(sets[0])
+                with torch.cuda.graph(grc, stream=side):
+                    for i in range(R):
+                        for n, f in stages:
+                            f(sets[(i + 1) % R])          # the last step of a replay runs on set 0
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            ok = True
+            for rep in range(3):
+                O.zero_(); st.idx.zero_()
+                torch.cuda.synchronize()
+                grc.replay()
+                torch.cuda.synchronize()
+                ok = ok and bool((O == ref_O).all()) and bool((st.idx == ref_idx).all())
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(3, args.steps // R)
+            e0.record()
+            for _ in range(reps):
+                grc.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t_g = e0.elapsed_time(e1) * 1e3 / (reps * R)
+            out["cold_step_graph_replay"] = {"us_per_step": round(t_g, 3),
+                                             "tokens_per_s_per_layer": round(cfg.B * Tq * cfg.L / (t_g * 1e-6), 1),
+                                             "replays_equal_eager": ok}
+            del grc
+        except Exception as ex:  # a reporting extra: never fail the bench on it
+            out["cold_step_graph_replay"] = {"error": str(ex)[:200]}
+
     # ---- the paper's literal retention rule (section 3.2): keep a chunk iff gate >= tau, with tau at the
     # score quantile that keeps the paper's average retention ratio (0.687, section 4.1) ----
     if not args.only:

@@ -138,9 +138,9 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
 // W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch.
 static size_t lstm_ws_pack(const kvev_shape *sh)
 {
-    // packed W_hh and W_ih (2 bytes per element), then a word per layer (max |W_hh|), padded to 256 bytes
+    // packed W_hh and W_ih (2 bytes per element), then 32 words per layer (partial maxima of |W_hh|), padded to 256 bytes
     return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 +
-                                     ((size_t)sh->L * 8 + 255) / 256 * 256
+                                     ((size_t)sh->L * 32 * 4 + 255) / 256 * 256
                                : 0;
 }
 

@@ -37,7 +37,7 @@ struct LstmArgs {
     float *h, *c, *util, *gate;
     float *xproj;         // workspace: fp32 input projections of a block of steps (fragment layout)
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *whh_packed;   // workspace: W_hh in fragment order (16-byte pieces; fp16 inside)
-    uint32_t *whh_max_bits;   // workspace: per layer the bit pattern of max |W_hh| (fixes the power-of-two scale)
+    uint32_t *whh_max_bits;   // workspace: 32 partial maxima of |W_hh| per layer as bit patterns (their maximum fixes the power-of-two scale)
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *wih_packed;   // workspace: W_ih in fragment order
     int L, BH, d, N_cap, d_g;
     int c0, c1;

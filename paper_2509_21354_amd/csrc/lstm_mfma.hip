@@ -129,10 +129,18 @@ __device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, 
 // LDS (every wave needs all of them as the B operand); a wave keeps the 2d-long weight rows of one (unit tile,
 // gate) in registers and walks the TT steps with them.  Its output is the bulk of the traffic (4*d_g floats per
 // sequence and step), written as 1 KiB per wave-level store in the fragment layout the recurrence reads back.
+template <int DG> __device__ void pack_whh_blocks(const LstmArgs &a, int block, int nblocks);
+
+// (ny_proj rows of the grid project; the rows after them, present in a call's first launch only, re-lay W_hh
+// for the recurrence that follows: both only need what the preparation kernel left, so they share a launch)
 template <int DG, int D, int TT>
-__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb)
+__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb, int ny_proj)
 {
     constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT, XP = 2 * D + 8, THREADS = Geo<DG>::THREADS;
+    if ((int)blockIdx.y >= ny_proj) {
+        pack_whh_blocks<DG>(a, ((int)blockIdx.y - ny_proj) * gridDim.x + blockIdx.x, ((int)gridDim.y - ny_proj) * gridDim.x);
+        return;
+    }
     extern __shared__ __align__(16) unsigned char smem_in[];
     bf16_t *s_x = reinterpret_cast<bf16_t *>(smem_in);           // [TT][16][XP]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -201,14 +209,36 @@ __device__ __forceinline__ int whh_scale_exp(uint32_t max_bits)
     return k > 100 ? 100 : k < -100 ? -100 : k;
 }
 
-// Per layer: the largest finite |W_hh| as a bit pattern (non-negative floats order like unsigned
-// integers, so an integer atomic max is exact and order-independent).  kScaleBlocks workgroups per
-// layer; the slots are zeroed by the W_ih re-layout kernel that runs before.
+// Weight preparation, one launch: blocks [0, nb_wih) re-lay W_ih in A-fragment order for the input projection
+// ([layer][wave][unit tile][gate][k-step][lane][8]); the kScaleBlocks blocks per layer after them each write the
+// largest finite |W_hh| of their share of the layer as a bit pattern (non-negative floats order like unsigned
+// integers) into a slot of their own: no atomics, nothing to clear between calls.
 constexpr int kScaleBlocks = 32;
-__global__ __launch_bounds__(256) void lstm_whh_max_kernel(const bf16_t *W_hh, size_t per_layer, uint32_t *max_bits)
+template <int DG, int D>
+__global__ __launch_bounds__(256) void lstm_prep_kernel(const bf16_t *W_ih, bf16x8_t *wih_packed, const bf16_t *W_hh,
+                                                        uint32_t *max_bits, int L, int nb_wih)
 {
+    const int t = threadIdx.x;
+    if ((int)blockIdx.x < nb_wih) {
+        constexpr int NW = Geo<DG>::NW, UT = Geo<DG>::UT, KS = 2 * D / 32;
+        const size_t frag = (size_t)blockIdx.x * 256 + t;
+        const size_t total = (size_t)L * NW * UT * 4 * KS * 64;
+        if (frag >= total) return;
+        const int lane = frag % 64;
+        size_t r = frag / 64;
+        const int ks = r % KS; r /= KS;
+        const int q = r % 4; r /= 4;
+        const int ut = r % UT; r /= UT;
+        const int wave = r % NW;
+        const int l = (int)(r / NW);
+        const int n = lane & 15, g4 = lane >> 4;
+        const bf16_t *src = W_ih + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * 2 * D + ks * 32 + g4 * 8;
+        wih_packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
+        return;
+    }
     __shared__ float s_max[4];
-    const int l = blockIdx.x / kScaleBlocks, part = blockIdx.x % kScaleBlocks, t = threadIdx.x;
+    const int b = (int)blockIdx.x - nb_wih, l = b / kScaleBlocks, part = b % kScaleBlocks;
+    constexpr size_t per_layer = (size_t)4 * DG * DG;
     const bf16_t *W = W_hh + (size_t)l * per_layer;
     float m = 0.f;
     for (size_t i = ((size_t)part * 256 + t) * 8; i < per_layer; i += (size_t)kScaleBlocks * 256 * 8) {
@@ -225,66 +255,51 @@ __global__ __launch_bounds__(256) void lstm_whh_max_kernel(const bf16_t *W_hh, s
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     if ((t & 63) == 0) s_max[t >> 6] = m;
     __syncthreads();
-    if (t == 0) {
-        m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-        atomicMax(max_bits + l, __float_as_uint(m));
-    }
+    if (t == 0) max_bits[b] = __float_as_uint(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3])));
+}
+
+// max |W_hh| of a layer from the kScaleBlocks partial maxima
+__device__ __forceinline__ uint32_t whh_layer_max(const uint32_t *max_bits, int l)
+{
+    uint32_t m = 0;
+#pragma unroll 8
+    for (int p = 0; p < kScaleBlocks; ++p) m = max(m, max_bits[l * kScaleBlocks + p]);
+    return m;
 }
 
 // W_hh scaled, converted to fp16 and re-laid in A-fragment order so that every
 // wave-level load of the recurrence is one contiguous 1 KiB piece (the row-major
 // matrix would give 16 half-used cache lines per load):
 // [layer][wave][item][gate][lane][8], items in the order the wave walks them.
-template <int DG>
-__global__ __launch_bounds__(256) void lstm_pack_whh_kernel(const bf16_t *W_hh, f16x8_t *packed, const uint32_t *max_bits, int L)
+// Run by `nblocks` workgroups of the input projection's first launch; one 16-byte fragment per thread and turn.
+template <int DG> __device__ void pack_whh_blocks(const LstmArgs &a, int block, int nblocks)
 {
     using G = Geo<DG>;
-    constexpr int NW = G::NW, UT = G::UT;
-    const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;         // one 16-byte fragment per thread
-    const size_t total = (size_t)L * NW * G::ITEMS * 4 * 64;
-    if (frag >= total) return;
-    const int lane = frag % 64;
-    size_t r = frag / 64;
-    const int q = r % 4; r /= 4;
-    const int item = r % G::ITEMS; r /= G::ITEMS;
-    const int ut = G::ut_of(item), ks = G::ks_of(item);
-    const int wave = r % NW;
-    const int l = (int)(r / NW);
-    const int n = lane & 15, g4 = lane >> 4;
-    const bf16_t *src = W_hh + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * DG + ks * 32 + g4 * 8;
-    const uint4 v = *reinterpret_cast<const uint4 *>(src);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    const float sc = ldexpf(1.f, whh_scale_exp(max_bits[l]));
-    f16x8_t o;
+    constexpr int NW = G::NW, UT = G::UT, THREADS = G::THREADS;
+    const bf16_t *W_hh = static_cast<const bf16_t *>(a.W_hh);
+    f16x8_t *packed = reinterpret_cast<f16x8_t *>(const_cast<bf16x8_t *>(a.whh_packed));
+    const size_t total = (size_t)a.L * NW * G::ITEMS * 4 * 64;
+    for (size_t frag = (size_t)block * THREADS + threadIdx.x; frag < total; frag += (size_t)nblocks * THREADS) {
+        const int lane = frag % 64;
+        size_t r = frag / 64;
+        const int q = r % 4; r /= 4;
+        const int item = r % G::ITEMS; r /= G::ITEMS;
+        const int ut = G::ut_of(item), ks = G::ks_of(item);
+        const int wave = r % NW;
+        const int l = (int)(r / NW);
+        const int n = lane & 15, g4 = lane >> 4;
+        const bf16_t *src = W_hh + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * DG + ks * 32 + g4 * 8;
+        const uint4 v = *reinterpret_cast<const uint4 *>(src);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const float sc = ldexpf(1.f, whh_scale_exp(whh_layer_max(a.whh_max_bits, l)));
+        f16x8_t o;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        o[2 * j] = (f16_t)(__uint_as_float(w[j] << 16) * sc);
-        o[2 * j + 1] = (f16_t)(__uint_as_float(w[j] & 0xFFFF0000u) * sc);
+        for (int j = 0; j < 4; ++j) {
+            o[2 * j] = (f16_t)(__uint_as_float(w[j] << 16) * sc);
+            o[2 * j + 1] = (f16_t)(__uint_as_float(w[j] & 0xFFFF0000u) * sc);
+        }
+        packed[frag] = o;
     }
-    packed[frag] = o;
-}
-
-// W_ih in A-fragment order for the input projection: [layer][wave][unit tile][gate][k-step][lane][8].
-template <int DG, int D>
-__global__ __launch_bounds__(256) void lstm_pack_wih_kernel(const bf16_t *W_ih, bf16x8_t *packed, int L, uint32_t *whh_max_bits)
-{
-    // (first job of the call: clear the per-layer maxima that the next kernel accumulates)
-    if (blockIdx.x == 0)
-        for (int i = threadIdx.x; i < L; i += 256) whh_max_bits[i] = 0u;
-    constexpr int NW = Geo<DG>::NW, UT = Geo<DG>::UT, KS = 2 * D / 32;
-    const size_t frag = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t total = (size_t)L * NW * UT * 4 * KS * 64;
-    if (frag >= total) return;
-    const int lane = frag % 64;
-    size_t r = frag / 64;
-    const int ks = r % KS; r /= KS;
-    const int q = r % 4; r /= 4;
-    const int ut = r % UT; r /= UT;
-    const int wave = r % NW;
-    const int l = (int)(r / NW);
-    const int n = lane & 15, g4 = lane >> 4;
-    const bf16_t *src = W_ih + ((size_t)l * 4 * DG + q * DG + wave * 16 * UT + ut * 16 + n) * 2 * D + ks * 32 + g4 * 8;
-    packed[frag] = *reinterpret_cast<const bf16x8_t *>(src);
 }
 
 template <int DG>
@@ -311,7 +326,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 
     const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
     const float b_s = bf16_to_f32(static_cast<const bf16_t *>(a.b_s)[l]);
-    const float inv_scale = ldexpf(1.f, -whh_scale_exp(a.whh_max_bits[l]));   // undoes the power-of-two scaling of the packed W_hh
+    const float inv_scale = ldexpf(1.f, -whh_scale_exp(whh_layer_max(a.whh_max_bits, l)));   // undoes the power-of-two scaling of the packed W_hh
 
     // state of (sequence n, units 16*UT*wave + 16*ut + 4*g4 + r) lives in this lane
     float c_reg[UT][4], h_reg[UT][4], ws_reg[UT][4];
@@ -495,33 +510,38 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         attr_set = true;
     }
     {
-        const size_t frags = (size_t)a.L * 4 * DG * DG / 8;
         const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
+        const int nb_wih = (int)((frags_i + 255) / 256);
+        const dim3 grid_p((unsigned)(nb_wih + a.L * kScaleBlocks));
         if (a.d == 64)
-            hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 64>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
-                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L, a.whh_max_bits);
+            hipLaunchKernelGGL((lstm_prep_kernel<DG, 64>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
+                               const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
         else
-            hipLaunchKernelGGL((lstm_pack_wih_kernel<DG, 128>), dim3((unsigned)((frags_i + 255) / 256)), dim3(256), 0, st,
-                               static_cast<const bf16_t *>(a.W_ih), const_cast<bf16x8_t *>(a.wih_packed), a.L, a.whh_max_bits);
-        hipLaunchKernelGGL(lstm_whh_max_kernel, dim3((unsigned)a.L * kScaleBlocks), dim3(256), 0, st,
-                           static_cast<const bf16_t *>(a.W_hh), (size_t)4 * DG * DG, a.whh_max_bits);
-        hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)((frags + 255) / 256)), dim3(256), 0, st,
-                           static_cast<const bf16_t *>(a.W_hh),
-                           reinterpret_cast<f16x8_t *>(const_cast<bf16x8_t *>(a.whh_packed)), a.whh_max_bits, a.L);
+            hipLaunchKernelGGL((lstm_prep_kernel<DG, 128>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
+                               const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
     }
+    // W_hh fragments of the whole call: 16 bytes per thread and turn, about 4 turns per packing workgroup
+    const size_t frags_h = (size_t)a.L * 4 * DG * DG / 8;
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
         // few sequences: shorter runs of steps per workgroup so that the launch still covers the chip
         const bool small = (size_t)groups * ((nb + kTT - 1) / kTT) < 256;
         const int tt = small ? 2 : kTT;
-        const dim3 grid_in(groups, (unsigned)((nb + tt - 1) / tt));
+        const int ny_proj = (nb + tt - 1) / tt;
+        int ny_pack = 0;
+        if (t0 == a.c0) {
+            const size_t want = (frags_h + (size_t)4 * Geo<DG>::THREADS - 1) / ((size_t)4 * Geo<DG>::THREADS);
+            ny_pack = (int)((want + groups - 1) / groups);
+            if (ny_pack > 4096) ny_pack = 4096;
+        }
+        const dim3 grid_in(groups, (unsigned)(ny_proj + ny_pack));
         const size_t lds_in = (size_t)tt * 16 * (2 * a.d + 8) * sizeof(bf16_t);
         if (a.d == 64) {
-            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
-            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
         } else {
-            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
-            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
         }
         hipLaunchKernelGGL((lstm_rec_kernel<DG>), dim3(groups), dim3(Geo<DG>::THREADS), lds, st, a, t0, nb);
     }

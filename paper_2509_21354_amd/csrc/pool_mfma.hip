@@ -30,9 +30,12 @@ __device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t &hi, ui
     lo = pack_bf16x2(r0 - __uint_as_float(mid << 16), r1 - __uint_as_float(mid & 0xFFFF0000u));
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
+// NW waves per workgroup: 4 when the launch fills the chip several times over, 16 (one tile row per wave) when
+// there are few tiles, so that a compute unit still has enough loads in flight.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void pool_mfma_kernel(PoolArgs a)
 {
+    constexpr int RPW = 16 / NW;         // tile rows per wave
     constexpr int EPL = D / 16;          // elements per lane of a 16-lane row group
     constexpr int XP = D + 8;            // padded bf16 row of a mean plane
     extern __shared__ __align__(16) bf16_t smem[];
@@ -52,8 +55,8 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
     const bool is_max = a.mode == KVEV_POOL_MAX;
 
     // ---- 1. stream the chunks, fp32 means to LDS ------------------------------
-    for (int i = 0; i < 4; ++i) {
-        const int rt = wave * 4 + i;                         // row within the tile
+    for (int i = 0; i < RPW; ++i) {
+        const int rt = wave * RPW + i;                       // row within the tile
         const int r = min(row0 + rt, rows_per_layer - 1);    // clamped: a tail row repeats the last one
         const size_t s = (size_t)l * a.BH + r / nch;
         const int c = a.c0 + r % nch;
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
     bf16_t *Kb = static_cast<bf16_t *>(a.Kbar), *Vb = static_cast<bf16_t *>(a.Vbar);
 
     if (a.mode != KVEV_POOL_MLP) {      // mean or maximum: the tile rows are the output (a bf16 maximum is its own hi term)
-        for (int i = tid; i < 2 * 16 * (D / 2); i += 256) {
+        for (int i = tid; i < 2 * 16 * (D / 2); i += 64 * NW) {
             const int kv = i / (16 * (D / 2)), rt = (i / (D / 2)) % 16, e = (i % (D / 2)) * 2;
             const int r = row0 + rt;
             if (r < rows_per_layer) {
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
     // ---- 2. layer 1: act = GELU(W1 xbar + b1), tiles of 16 hidden units ------
     const int ds = a.d_sum;
     const int tiles1 = ds / 16;
-    for (int t = wave; t < 2 * tiles1; t += 4) {
+    for (int t = wave; t < 2 * tiles1; t += NW) {
         const int kv = t / tiles1, u0 = (t % tiles1) * 16;
         const bf16_t *W1 = static_cast<const bf16_t *>(kv ? a.W1V : a.W1K) + ((size_t)l * ds + u0 + n) * D + g4 * 8;
         const bf16_t *b1 = static_cast<const bf16_t *>(kv ? a.b1V : a.b1K) + (size_t)l * ds + u0 + 4 * g4;
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256) void pool_mfma_kernel(PoolArgs a)
 
     // ---- 3. layer 2: summary = W2 act + b2, tiles of 16 output elements ------
     constexpr int tiles2 = D / 16;
-    for (int t = wave; t < 2 * tiles2; t += 4) {
+    for (int t = wave; t < 2 * tiles2; t += NW) {
         const int kv = t / tiles2, e0 = (t % tiles2) * 16;
         const bf16_t *W2 = static_cast<const bf16_t *>(kv ? a.W2V : a.W2K) + ((size_t)l * D + e0 + n) * ds + g4 * 8;
         const bf16_t *b2 = static_cast<const bf16_t *>(kv ? a.b2V : a.b2K) + (size_t)l * D + e0 + 4 * g4;
@@ -206,10 +209,14 @@ hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st)
     const size_t blocks = (size_t)a.L * ((rows_per_layer + 15) / 16);
     if (blocks == 0) return hipSuccess;
     const size_t lds = sizeof(bf16_t) * 3 * 2 * 16 * (((size_t)a.d + 8) + ((size_t)a.d_sum + 8));
-    if (a.d == 64)
-        hipLaunchKernelGGL((pool_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL((pool_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    const bool few = blocks < 2048;          // fewer than 8 tiles per compute unit
+    if (a.d == 64) {
+        if (few) hipLaunchKernelGGL((pool_mfma_kernel<64, 16>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
+        else hipLaunchKernelGGL((pool_mfma_kernel<64, 4>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    } else {
+        if (few) hipLaunchKernelGGL((pool_mfma_kernel<128, 16>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
+        else hipLaunchKernelGGL((pool_mfma_kernel<128, 4>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    }
     return hipGetLastError();
 }
 
