@@ -562,12 +562,17 @@ int kvo_retain(int dtype, int S, int d, int k, int k_cap, const void *Kbar_new, 
 
 /* Eq. 1 over a compact store: rows 0..count-1 of Kc/Vc [S,k_cap,d] (the kept
  * summaries, ascending chunk id) followed by rows 0..win_len-1 of the resident
- * raw window Kw/Vw [S,W_cap,d].  Same arithmetic as kvo_gated_attention. */
+ * raw window Kw/Vw [S,W_cap,d].  Same arithmetic as kvo_gated_attention.
+ * causal != 0 (strict causality, section 3.2): the Tq queries are the window's
+ * last Tq tokens, and query i sees the store and the window rows up to its own,
+ * i.e. all rows but the last Tq - 1 - i. */
 int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, int W_cap, const void *Q,
                           int Tq, const void *Kw, const void *Vw, const void *Kc, const void *Vc,
-                          const int32_t *count, int k_cap, void *O)
+                          const int32_t *count, int k_cap, int causal, void *O)
 {
     if (L < 1 || B < 1 || H < 1 || d < 1 || win_len < 0 || win_len > W_cap || Tq < 0 || k_cap < 0)
+        return KVO_BAD_ARG;
+    if (causal && Tq > win_len)
         return KVO_BAD_ARG;
     int n_max = k_cap + win_len;
     const void **kb = malloc(sizeof(void *) * (size_t)(n_max + 1));
@@ -584,7 +589,7 @@ int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, in
         for (int t = 0; t < win_len; ++t) { kb[n] = Kw; vb[n] = Vw; off[n] = (s * W_cap + (size_t)t) * d; ++n; }
         for (int i = 0; i < Tq; ++i) {
             size_t qo = (s * Tq + i) * d;
-            attend_rows(dtype, d, Q, qo, kb, vb, off, n, O, qo, logit, acc, NULL);
+            attend_rows(dtype, d, Q, qo, kb, vb, off, causal ? n - (Tq - 1 - i) : n, O, qo, logit, acc, NULL);
         }
     }
     free(kb);

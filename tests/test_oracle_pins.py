@@ -543,6 +543,16 @@ def test_compact_attention_equals_gated_attention_on_the_gathered_rows(oracle):
             Vc[s_][:m] = r["Vbar"][s_][r["idx"][s_][:m]]
         O = oracle.compact_attention(t["Q"], Kw, Vw, cfg.T - win0, Kc, Vc, r["count"])
         assert (O == r["O"]).all()
+        # a causal frame over the compact store = the causal frame over the indexed caches, and its last
+        # query (which sees everything) = the plain one
+        Tq = min(3, cfg.T - win0)
+        Qf = np.ascontiguousarray(np.repeat(oracle.to_np(t["Q"])[..., :1, :], Tq, axis=3))
+        Oc = oracle.compact_attention(Qf, Kw, Vw, cfg.T - win0, Kc, Vc, r["count"], causal=1)
+        Oi = oracle.attention_ext(Qf, t["K"], t["V"], cfg.T, cfg.C, cfg.W, r["Kbar"], r["Vbar"], r["idx"], r["count"], causal=1)
+        assert (Oc == Oi).all()
+        assert (Oc[..., Tq - 1, :] == O[..., 0, :]).all() and not (Oc[..., 0, :] == O[..., 0, :]).all()
+        with pytest.raises(ValueError):
+            oracle.compact_attention(np.repeat(Qf, cfg.T, axis=3), Kw, Vw, cfg.T - win0, Kc, Vc, r["count"], causal=1)
         # resident rows: k + window instead of T (the memory ratio of section 3.4)
         assert Kc.shape[3] - 1 + Kw.shape[3] == cfg.k + cfg.T - win0 < cfg.T
 
