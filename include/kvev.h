@@ -181,11 +181,13 @@ int kvev_retain(const kvev_shape *shape, int k, int k_cap, const void *Kbar_new,
  * raw buffer: Kw, Vw are [L,B,H,T_cap,d] and hold the window's tokens in rows
  * 0 .. T-1 (C, W, N_cap of the shape are not used).  Same arithmetic, row order
  * and rounding as kvev_gated_attention over the same rows, so the two give the
- * same bits.  Workspace: kvev_workspace_bytes(KVEV_OP_COMPACT_ATTENTION, shape,
- * Tq, k_cap). */
+ * same bits.  causal as in kvev_gated_attention: 1 = the Tq queries are the
+ * window's last Tq tokens (needs Tq <= T), each seeing the store and the window
+ * rows up to its own.  Workspace: kvev_workspace_bytes(KVEV_OP_COMPACT_ATTENTION,
+ * shape, Tq, k_cap). */
 int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const void *Kw, const void *Vw,
-                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, void *O,
-                           void *ws, size_t ws_bytes, void *stream);
+                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, int causal,
+                           void *O, void *ws, size_t ws_bytes, void *stream);
 
 /* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape.  `n` is Tq
  * for the attention ops and chunk_end - chunk_begin for pool / gate; k_cap is

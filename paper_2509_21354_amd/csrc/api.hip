@@ -98,7 +98,6 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
         return KVEV_ERR_INVALID_ARG;
     if (gated && !compact && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
     if (causal != 0 && causal != 1) return KVEV_ERR_INVALID_ARG;
-    if (causal && compact) return KVEV_ERR_UNSUPPORTED;
     if (Tq == 0) return KVEV_OK;
     if ((int64_t)sh->L * sh->B * sh->H * Tq > (int64_t)1 << 26) return KVEV_ERR_INVALID_ARG;
 
@@ -281,10 +280,10 @@ int kvev_dense_attention(const kvev_shape *sh, const void *Q, int Tq, const void
 }
 
 int kvev_compact_attention(const kvev_shape *sh, const void *Q, int Tq, const void *Kw, const void *Vw,
-                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, void *O, void *ws,
-                           size_t ws_bytes, void *stream)
+                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, int causal, void *O,
+                           void *ws, size_t ws_bytes, void *stream)
 {
-    return attention_common(sh, Q, Tq, Kw, Vw, Kc, Vc, nullptr, count, k_cap, 2, 0, O, ws, ws_bytes, stream);
+    return attention_common(sh, Q, Tq, Kw, Vw, Kc, Vc, nullptr, count, k_cap, 2, causal, O, ws, ws_bytes, stream);
 }
 
 int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, const void *Vbar_new,

@@ -104,6 +104,15 @@ def test_compact_attention_gives_the_bits_of_the_indexed_attention(number, Tq):
     assert (_bits(O2) == _bits(O)).all()
     ref = orc.compact_attention(t["Q"], Kw.cpu(), Vw.cpu(), cfg.T - win0, Kc.cpu(), Vc.cpu(), cnt.cpu())
     assert_close_storage(O2, ref, cfg.dtype, "O (compact store)")
+    # a causal frame (the queries are the window's last Tq tokens): same bits as the indexed causal form, and the oracle's values
+    if Tq > 1:
+        O3, O4 = torch.empty_like(O), torch.empty_like(O)
+        kb.kvev_gated_attention(st.shape, g["Q"], Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, O3, st.ws, causal=1)
+        kb.kvev_compact_attention(shw, g["Q"], Tq, Kw, Vw, Kc, Vc, cnt, k_cap, O4, ws, causal=1)
+        torch.cuda.synchronize()
+        assert (_bits(O4) == _bits(O3)).all() and not (_bits(O4) == _bits(O2)).all()
+        ref_c = orc.compact_attention(t["Q"], Kw.cpu(), Vw.cpu(), cfg.T - win0, Kc.cpu(), Vc.cpu(), cnt.cpu(), causal=1)
+        assert_close_storage(O4, ref_c, cfg.dtype, "O (compact store, causal frame)")
 
 
 def test_evicting_stream_equals_the_full_cache_stream():
