@@ -30,13 +30,15 @@ __device__ __forceinline__ size_t query_row(const AttnArgs &a, int s, int r)
 
 // NQ queries of one key-value sequence per workgroup: every row that is loaded
 // serves all of them (what grouped-query heads and short query frames are for).
-template <typename T, int D, int U, int NQ>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
+// NW waves per workgroup: 4 normally; 16 when the launch has fewer workgroups than the chip has compute units
+// (a short cache and few sequences: the rows of a sequence are then spread over four times the lanes).
+template <typename T, int D, int U, int NQ, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
 {
-    constexpr int EPL = D / 16;
+    constexpr int EPL = D / 16, GROUPS = 4 * NW;     // 16-lane row groups per workgroup
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
-    const int grp = tid >> 4;      // row group within the workgroup, 0..15
+    const int grp = tid >> 4;      // row group within the workgroup, 0 .. GROUPS-1
     const int cl = tid & 15;       // column lane within the group
     const int R = a.G * a.Tq;
     const int qgroups = (R + NQ - 1) / NQ;
@@ -86,12 +88,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
     const size_t seq_sum = (size_t)s * a.N_cap;
     const int32_t *idx = a.idx ? a.idx + (size_t)s * a.k_cap : nullptr;   // null: the store is compact, row j is entry j
 
-    for (int base = j0; base < j1; base += 16 * U) {
+    for (int base = j0; base < j1; base += GROUPS * U) {
         Raw<T, EPL> kr[U], vr[U];
         int jrow[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int j = base + grp + 16 * u;
+            int j = base + grp + GROUPS * u;
             jrow[u] = j < j1 ? j : n;          // n: beyond every query's limit
             j = j < j1 ? j : j1 - 1;
             size_t off;
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
         }
     }
 
-    __shared__ float s_m[NQ][4], s_l[NQ][4], s_o[NQ][4][D];
+    __shared__ float s_m[NQ][NW], s_l[NQ][NW], s_o[NQ][NW][D];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
         // merge the 4 lane groups of the wave
@@ -176,10 +178,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a)
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
             if (!qok[i]) continue;
-            const float M = fmaxf(fmaxf(s_m[i][0], s_m[i][1]), fmaxf(s_m[i][2], s_m[i][3]));
+            float M = s_m[i][0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[i][w]);
             float L = 0.f, acc = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < NW; ++w) {
                 const float f = exp2f(s_m[i][w] - M);
                 L += s_l[i][w] * f;
                 acc += s_o[i][w][tid] * f;
@@ -250,7 +254,10 @@ static hipError_t launch_decode_q(const AttnArgs &a, hipStream_t st)
     const int R = a.G * a.Tq;
     const size_t blocks = (size_t)a.S * ((R + NQ - 1) / NQ) * a.nsplit;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (blocks < 256 && a.rows_per_split > 64)
+        hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 16>), dim3((unsigned)blocks), dim3(1024), 0, st, a);
+    else
+        hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 4>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     if (a.nsplit > 1)
         hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * R)), dim3(D),
                            (size_t)a.nsplit * sizeof(float), st, a, a.part, a.nsplit, static_cast<T *>(a.O));
