@@ -566,11 +566,12 @@ int kvo_retain(int dtype, int S, int d, int k, int k_cap, const void *Kbar_new, 
  * causal != 0 (strict causality, section 3.2): the Tq queries are the window's
  * last Tq tokens, and query i sees the store and the window rows up to its own,
  * i.e. all rows but the last Tq - 1 - i. */
-int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, int W_cap, const void *Q,
+int kvo_compact_attention(int dtype, int L, int B, int H, int H_kv, int d, int win_len, int W_cap, const void *Q,
                           int Tq, const void *Kw, const void *Vw, const void *Kc, const void *Vc,
                           const int32_t *count, int k_cap, int causal, void *O)
 {
-    if (L < 1 || B < 1 || H < 1 || d < 1 || win_len < 0 || win_len > W_cap || Tq < 0 || k_cap < 0)
+    /* grouped-query heads as in kvo_attention_ext: Q, O have H heads; store, window and count H_kv */
+    if (L < 1 || B < 1 || H < 1 || H_kv < 1 || H % H_kv != 0 || d < 1 || win_len < 0 || win_len > W_cap || Tq < 0 || k_cap < 0)
         return KVO_BAD_ARG;
     if (causal && Tq > win_len)
         return KVO_BAD_ARG;
@@ -582,13 +583,15 @@ int kvo_compact_attention(int dtype, int L, int B, int H, int d, int win_len, in
     double *acc = malloc(sizeof(double) * (size_t)d);
     int rc = KVO_OK;
     size_t S = (size_t)L * B * H;
-    for (size_t s = 0; s < S; ++s) {
+    int G = H / H_kv;
+    for (size_t sq = 0; sq < S; ++sq) {
+        size_t s = (sq / H) * H_kv + (sq % H) / G;       /* the key-value head this query head reads */
         int m = count[s], n = 0;
         if (m < 0 || m > k_cap) { rc = KVO_BAD_ARG; break; }
         for (int j = 0; j < m; ++j) { kb[n] = Kc; vb[n] = Vc; off[n] = (s * k_cap + (size_t)j) * d; ++n; }
         for (int t = 0; t < win_len; ++t) { kb[n] = Kw; vb[n] = Vw; off[n] = (s * W_cap + (size_t)t) * d; ++n; }
         for (int i = 0; i < Tq; ++i) {
-            size_t qo = (s * Tq + i) * d;
+            size_t qo = (sq * Tq + i) * d;
             attend_rows(dtype, d, Q, qo, kb, vb, off, causal ? n - (Tq - 1 - i) : n, O, qo, logit, acc, NULL);
         }
     }

@@ -224,7 +224,7 @@ def compact_attention(Q, Kw, Vw, win_len, Kc, Vc, count, causal=0):
     count = np.ascontiguousarray(to_np(count), dtype=np.int32)
     L, B, H, Tq, d = Q.shape
     O = np.zeros_like(Q)
-    rc = lib().kvo_compact_attention(dtype_code(Q), L, B, H, d, win_len, Kw.shape[3], _p(Q), Tq, _p(Kw), _p(Vw),
+    rc = lib().kvo_compact_attention(dtype_code(Q), L, B, H, Kw.shape[2], d, win_len, Kw.shape[3], _p(Q), Tq, _p(Kw), _p(Vw),
                                      _p(Kc), _p(Vc), _p(count), Kc.shape[3], int(causal), _p(O))
     _check(rc, "compact_attention")
     return O

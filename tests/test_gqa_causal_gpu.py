@@ -68,6 +68,27 @@ def test_chain_and_attention_with_grouped_heads_and_causal_frames(cfg, causal):
     assert_close_storage(O, ref, cfg.dtype, "O gated")
     refd = orc.attention_ext(t["Q"], t["K"], t["V"], cfg.T, causal=causal)
     assert_close_storage(Od, refd, cfg.dtype, "O dense")
+    # after eviction (per key-value head): compact store + window buffer give the bits of the indexed form
+    n_cand, win0 = cfg.N_cand, cfg.N_cand * cfg.C
+    lead = (cfg.L, cfg.B, cfg.kv_heads)
+    k_cap = cfg.k + 1
+    if n_cand > 0 and k_cap + n_cand <= 4000:
+        Kc = torch.zeros(lead + (k_cap, cfg.d), dtype=cfg.torch_dtype, device="cuda")
+        Vc = torch.zeros_like(Kc)
+        ids = torch.full(lead + (k_cap,), -1, dtype=torch.int32, device="cuda")
+        uc = torch.zeros(lead + (k_cap,), dtype=torch.float32, device="cuda")
+        cnt = torch.zeros(lead, dtype=torch.int32, device="cuda")
+        kb.kvev_retain(sh, cfg.k, k_cap, st.Kbar, st.Vbar, st.util, st.N_cap, 0, n_cand, Kc, Vc, ids, uc, cnt)
+        Kw = g["K"][..., win0:cfg.T, :].contiguous()
+        Vw = g["V"][..., win0:cfg.T, :].contiguous()
+        shw = kb.make_shape(cfg, T=cfg.T - win0, T_cap=cfg.T - win0, N_cap=k_cap)
+        wsw = kb.alloc_workspace(kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, shw, cfg.Tq, k_cap))
+        Oc = torch.empty_like(O)
+        kb.kvev_compact_attention(shw, g["Q"], cfg.Tq, Kw, Vw, Kc, Vc, cnt, k_cap, Oc, wsw, causal=causal)
+        torch.cuda.synchronize()
+        assert (orc.to_np(Oc) == orc.to_np(O)).all()
+        refc = orc.compact_attention(t["Q"], Kw.cpu(), Vw.cpu(), cfg.T - win0, Kc.cpu(), Vc.cpu(), cnt.cpu(), causal=causal)
+        assert_close_storage(Oc, refc, cfg.dtype, "O compact store")
     if causal:
         # the last query of a causal frame sees everything: same bits as the frame without the mask
         On = torch.empty_like(O)

@@ -578,6 +578,19 @@ def test_grouped_query_and_causal_attention(oracle):
     Om = oracle.gated_attention(t["Q"], rep(K2), rep(V2), rep(Kb2), rep(Vb2), rep(i2), rep(c2), cfg.T, cfg.C, cfg.W)
     assert (Og == Om).all()
     assert (oracle.attention_ext(t["Q"], K2, V2, cfg.T) == oracle.dense_attention(t["Q"], rep(K2), rep(V2), cfg.T)).all()
+    # the compact store with grouped heads: the rows gathered per key-value head, read by the group's query heads
+    win0 = cfg.N_cand * cfg.C
+    Kw2 = np.ascontiguousarray(oracle.to_np(K2)[..., win0:cfg.T, :])
+    Vw2 = np.ascontiguousarray(oracle.to_np(V2)[..., win0:cfg.T, :])
+    Kc2 = np.zeros(Kb2.shape[:3] + (cfg.k, cfg.d), Kb2.dtype)
+    Vc2 = np.zeros_like(Kc2)
+    for s_ in np.ndindex(Kb2.shape[:3]):
+        m = c2[s_]
+        Kc2[s_][:m] = Kb2[s_][i2[s_][:m]]
+        Vc2[s_][:m] = Vb2[s_][i2[s_][:m]]
+    assert (oracle.compact_attention(t["Q"], Kw2, Vw2, cfg.T - win0, Kc2, Vc2, c2) == Og).all()
+    Ogc = oracle.attention_ext(t["Q"], K2, V2, cfg.T, cfg.C, cfg.W, Kb2, Vb2, i2, c2, causal=1)
+    assert (oracle.compact_attention(t["Q"], Kw2, Vw2, cfg.T - win0, Kc2, Vc2, c2, causal=1) == Ogc).all()
     # --- causal: query i == one query over the cache cut at its own position
     Oc = oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T, cfg.C, cfg.W, r["Kbar"], r["Vbar"], r["idx"], r["count"], causal=1)
     Od = oracle.attention_ext(t["Q"], t["K"], t["V"], cfg.T, causal=1)
