@@ -30,7 +30,7 @@ __device__ __forceinline__ size_t query_row(const AttnArgs &a, int s, int r)
 
 // NQ queries of one key-value sequence per workgroup: every row that is loaded
 // serves all of them (what grouped-query heads and short query frames are for).
-// NW waves per workgroup: 4 normally; 16 when the launch has fewer workgroups than the chip has compute units
+// NW waves per workgroup: 4 normally; 16 when the launch has no more workgroups than the chip has compute units
 // (a short cache and few sequences: the rows of a sequence are then spread over four times the lanes).
 template <typename T, int D, int U, int NQ, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
@@ -254,7 +254,7 @@ static hipError_t launch_decode_q(const AttnArgs &a, hipStream_t st)
     const int R = a.G * a.Tq;
     const size_t blocks = (size_t)a.S * ((R + NQ - 1) / NQ) * a.nsplit;
     if (blocks == 0) return hipSuccess;
-    if (blocks < 256 && a.rows_per_split > 64)
+    if (blocks <= 256 && a.rows_per_split > 64)
         hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 16>), dim3((unsigned)blocks), dim3(1024), 0, st, a);
     else
         hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 4>), dim3((unsigned)blocks), dim3(256), 0, st, a);
