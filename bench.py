@@ -408,7 +408,7 @@ def main():
             e = {"us": round(t_a, 3), "hbm_GBps": round(cost["pool"]["bytes"] / t_a / 1e3, 1)}
             if mode == kb.POOL_TOKEN_MLP:
                 # 2*C*d*d_sum flop per chunk and side on the matrix cores, C*d_sum GELUs per chunk and side on the
-                # vector ALUs (12 operations + one quarter-rate exp2 = 15 issue slots of 4 clocks per 64 of them)
+                # vector ALUs (11 operations + one quarter-rate exp2 = 15 issue slots of 4 clocks per 64 of them)
                 gelus = 2 * tokens * cfg.d_sum
                 peak = 256 * 4 * 2.4e9 * 64 / (15 * 4)
                 e.update({"layer1_TFLOPs": round(2 * tokens * 2 * cfg.d * cfg.d_sum / t_a / 1e6, 1),

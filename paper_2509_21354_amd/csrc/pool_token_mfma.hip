@@ -7,7 +7,7 @@
 //   summary = W2 * ( (1/C) sum_j GELU(W1 x_j + b1) ) + b2.
 // What is left per token is one d -> d_sum layer, a real dense contraction
 // (2*C*d*d_sum flop per chunk and side), and C*d_sum GELUs, which are what the
-// kernel's time goes into: one exp2 (quarter rate) and 12 vector operations each
+// kernel's time goes into: one exp2 (quarter rate) and 11 vector operations each
 // against 1/8 of an MFMA.
 //
 // A workgroup (16 waves) holds W1 of both sides of one layer in LDS and walks
@@ -29,7 +29,7 @@ namespace kvev {
 // GELU(z) = z Phi(z) = max(z, 0) - |z| E(|z|) = z/2 + |z| (1/2 - E(|z|)), E(u) = erfc(u / sqrt 2) / 2 = exp2(u P(u) - 1) with u clamped
 // to 4 sqrt 2 (E there is 7.7e-9): P is a 7-coefficient fit (fit_gelu_poly.py beside this file derives the
 // constants; |E_poly - E| < 9e-8 in fp32, i.e. the exact-erf GELU to fp32 accuracy).  Returns acc + GELU(z):
-// 12 vector operations and one exp2.
+// 11 vector operations and one exp2.
 __device__ __forceinline__ float add_gelu_poly(float acc, float z)
 {
     const float u = __builtin_amdgcn_fmed3f(fabsf(z), 0.f, 5.656854f);      // = min(|z|, 4 sqrt 2) in one operation
