@@ -23,6 +23,7 @@ def _bits(t):
     ("bf16", 128, 128, 130, (300, 40, 0, 257, 3)),          # more candidates than threads, several row batches
     ("f32", 128, 40, 40, (33, 64, 1)),
     ("bf16", 64, 0, 4, (5, 5)),                              # k = 0: nothing is ever kept
+    ("bf16", 64, 500, 512, (3488, 100, 3488)),               # the largest store + frame the entry point takes (4000)
 ])
 def test_retain_is_bit_exact(dtype, d, k, k_cap, frames):
     torch.manual_seed(11)

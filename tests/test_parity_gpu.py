@@ -109,7 +109,7 @@ def test_attention_empty_cases():
 
 
 @pytest.mark.parametrize("n_cand,k", [(0, 3), (1, 1), (63, 10), (64, 64), (65, 7), (120, 32), (504, 128),
-                                      (2000, 300), (130, 0), (77, 500)])
+                                      (2000, 300), (130, 0), (77, 500), (16384, 1000)])   # the last: the largest candidate set taken
 def test_select_topk_is_bit_exact(n_cand, k):
     C, W = 4, 8
     T = n_cand * C + W
