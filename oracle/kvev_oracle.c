@@ -562,14 +562,19 @@ int kvo_retain(int dtype, int S, int d, int k, int k_cap, const void *Kbar_new, 
 
 /* Eq. 1 over a compact store: rows 0..count-1 of Kc/Vc [S,k_cap,d] (the kept
  * summaries, ascending chunk id) followed by rows 0..win_len-1 of the resident
- * raw window Kw/Vw [S,W_cap,d].  Same arithmetic as kvo_gated_attention.
+ * raw window Kw/Vw [S,W_cap,d], a ring buffer that starts at row win_first
+ * (section 3.3: only the recent window stays uncompressed; a ring lets it advance
+ * without moving rows).  Same arithmetic as kvo_gated_attention.
  * causal != 0 (strict causality, section 3.2): the Tq queries are the window's
  * last Tq tokens, and query i sees the store and the window rows up to its own,
  * i.e. all rows but the last Tq - 1 - i. */
-int kvo_compact_attention(int dtype, int L, int B, int H, int H_kv, int d, int win_len, int W_cap, const void *Q,
-                          int Tq, const void *Kw, const void *Vw, const void *Kc, const void *Vc,
+int kvo_compact_attention(int dtype, int L, int B, int H, int H_kv, int d, int win_len, int W_cap, int win_first,
+                          const void *Q, int Tq, const void *Kw, const void *Vw, const void *Kc, const void *Vc,
                           const int32_t *count, int k_cap, int causal, void *O)
 {
+    /* the window buffer is a ring: its t-th token sits in row (win_first + t) mod W_cap */
+    if (win_first < 0 || (win_first > 0 && win_first >= W_cap))
+        return KVO_BAD_ARG;
     /* grouped-query heads as in kvo_attention_ext: Q, O have H heads; store, window and count H_kv */
     if (L < 1 || B < 1 || H < 1 || H_kv < 1 || H % H_kv != 0 || d < 1 || win_len < 0 || win_len > W_cap || Tq < 0 || k_cap < 0)
         return KVO_BAD_ARG;
@@ -589,7 +594,9 @@ int kvo_compact_attention(int dtype, int L, int B, int H, int H_kv, int d, int w
         int m = count[s], n = 0;
         if (m < 0 || m > k_cap) { rc = KVO_BAD_ARG; break; }
         for (int j = 0; j < m; ++j) { kb[n] = Kc; vb[n] = Vc; off[n] = (s * k_cap + (size_t)j) * d; ++n; }
-        for (int t = 0; t < win_len; ++t) { kb[n] = Kw; vb[n] = Vw; off[n] = (s * W_cap + (size_t)t) * d; ++n; }
+        for (int t = 0; t < win_len; ++t) {
+            kb[n] = Kw; vb[n] = Vw; off[n] = (s * W_cap + (size_t)((win_first + t) % W_cap)) * d; ++n;
+        }
         for (int i = 0; i < Tq; ++i) {
             size_t qo = (sq * Tq + i) * d;
             attend_rows(dtype, d, Q, qo, kb, vb, off, causal ? n - (Tq - 1 - i) : n, O, qo, logit, acc, NULL);

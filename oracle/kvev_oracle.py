@@ -217,14 +217,14 @@ def retain(Kbar_new, Vbar_new, util_new, first_chunk, n_new, k, Kc, Vc, chunk_id
     _check(rc, "retain")
 
 
-def compact_attention(Q, Kw, Vw, win_len, Kc, Vc, count, causal=0):
+def compact_attention(Q, Kw, Vw, win_len, Kc, Vc, count, causal=0, win_first=0):
     """Eq. 1 over kept summaries (compact store) + resident raw window; causal: the queries are the
-    window's last Tq tokens."""
+    window's last Tq tokens; win_first: the window buffer is a ring that starts at this row."""
     Q, Kw, Vw, Kc, Vc = (to_np(x) for x in (Q, Kw, Vw, Kc, Vc))
     count = np.ascontiguousarray(to_np(count), dtype=np.int32)
     L, B, H, Tq, d = Q.shape
     O = np.zeros_like(Q)
-    rc = lib().kvo_compact_attention(dtype_code(Q), L, B, H, Kw.shape[2], d, win_len, Kw.shape[3], _p(Q), Tq, _p(Kw), _p(Vw),
+    rc = lib().kvo_compact_attention(dtype_code(Q), L, B, H, Kw.shape[2], d, win_len, Kw.shape[3], int(win_first), _p(Q), Tq, _p(Kw), _p(Vw),
                                      _p(Kc), _p(Vc), _p(count), Kc.shape[3], int(causal), _p(O))
     _check(rc, "compact_attention")
     return O

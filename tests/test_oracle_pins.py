@@ -553,6 +553,18 @@ def test_compact_attention_equals_gated_attention_on_the_gathered_rows(oracle):
         assert (Oc[..., Tq - 1, :] == O[..., 0, :]).all() and not (Oc[..., 0, :] == O[..., 0, :]).all()
         with pytest.raises(ValueError):
             oracle.compact_attention(np.repeat(Qf, cfg.T, axis=3), Kw, Vw, cfg.T - win0, Kc, Vc, r["count"], causal=1)
+        # the window as a ring: the same rows rotated inside a larger buffer, started at win_first
+        wl, cap, first = cfg.T - win0, cfg.T - win0 + 3, cfg.T - win0 - 2
+        Kr = np.zeros(Kw.shape[:3] + (cap, cfg.d), Kw.dtype)
+        Vr = np.zeros_like(Kr)
+        rows = (first + np.arange(wl)) % cap
+        Kr[..., rows, :] = Kw[..., :wl, :]
+        Vr[..., rows, :] = Vw[..., :wl, :]
+        assert rows.max() == cap - 1 and rows[-1] < rows[0]           # it does wrap
+        assert (oracle.compact_attention(t["Q"], Kr, Vr, wl, Kc, Vc, r["count"], win_first=first) == O).all()
+        assert (oracle.compact_attention(Qf, Kr, Vr, wl, Kc, Vc, r["count"], causal=1, win_first=first) == Oc).all()
+        with pytest.raises(ValueError):
+            oracle.compact_attention(t["Q"], Kr, Vr, wl, Kc, Vc, r["count"], win_first=cap)
         # resident rows: k + window instead of T (the memory ratio of section 3.4)
         assert Kc.shape[3] - 1 + Kw.shape[3] == cfg.k + cfg.T - win0 < cfg.T
 
