@@ -178,16 +178,19 @@ int kvev_retain(const kvev_shape *shape, int k, int k_cap, const void *Kbar_new,
 
 /* Eq. 1 over what is resident after eviction: rows 0 .. count-1 of the compact
  * store Kc / Vc followed by the raw window.  Here `shape` describes the resident
- * raw buffer: Kw, Vw are [L,B,H,T_cap,d] and hold the window's tokens in rows
- * 0 .. T-1 (C, W, N_cap of the shape are not used).  Same arithmetic, row order
+ * raw buffer: Kw, Vw are [L,B,H,T_cap,d], used as a ring: the window's t-th
+ * token, t = 0 .. T-1, sits in row (win_first + t) mod T_cap, so a caller appends
+ * new tokens behind the last one and advances win_first when chunks leave the
+ * window, without moving rows (win_first = 0: rows 0 .. T-1; needs
+ * 0 <= win_first < T_cap; C, W, N_cap of the shape are not used).  Same arithmetic, row order
  * and rounding as kvev_gated_attention over the same rows, so the two give the
  * same bits.  causal as in kvev_gated_attention: 1 = the Tq queries are the
  * window's last Tq tokens (needs Tq <= T), each seeing the store and the window
  * rows up to its own.  Workspace: kvev_workspace_bytes(KVEV_OP_COMPACT_ATTENTION,
  * shape, Tq, k_cap). */
 int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const void *Kw, const void *Vw,
-                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, int causal,
-                           void *O, void *ws, size_t ws_bytes, void *stream);
+                           int win_first, const void *Kc, const void *Vc, const int32_t *count, int k_cap,
+                           int causal, void *O, void *ws, size_t ws_bytes, void *stream);
 
 /* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape.  `n` is Tq
  * for the attention ops and chunk_end - chunk_begin for pool / gate; k_cap is

@@ -69,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.kvev_gated_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_dense_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, sz, vp]
         L.kvev_retain.argtypes = [shp, ci, ci, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
-        L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]
+        L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_workspace_bytes.argtypes = [ci, shp, ci, ci]
         L.kvev_workspace_bytes.restype = sz
         L.kvev_status_string.argtypes = [ci]
@@ -168,8 +168,8 @@ def kvev_retain(shape: Shape, k, k_cap, Kbar_new, Vbar_new, util_new, n_new_cap,
     _check(st, "kvev_retain")
 
 
-def kvev_compact_attention(shape: Shape, Q, Tq, Kw, Vw, Kc, Vc, count, k_cap, O, ws=None, causal=0):
-    st = lib().kvev_compact_attention(ctypes.byref(shape), _ptr(Q), Tq, _ptr(Kw), _ptr(Vw), _ptr(Kc), _ptr(Vc),
+def kvev_compact_attention(shape: Shape, Q, Tq, Kw, Vw, Kc, Vc, count, k_cap, O, ws=None, causal=0, win_first=0):
+    st = lib().kvev_compact_attention(ctypes.byref(shape), _ptr(Q), Tq, _ptr(Kw), _ptr(Vw), win_first, _ptr(Kc), _ptr(Vc),
                                       _ptr(count), k_cap, causal, _ptr(O), _ptr(ws),
                                       ws.numel() if ws is not None else 0, _stream())
     _check(st, "kvev_compact_attention")

@@ -86,7 +86,7 @@ static bool attn_takes_mq(const kvev_shape *sh, int Tq)
 static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
                             const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
                             int k_cap, int gated, int causal, void *O, void *ws, size_t ws_bytes,
-                            void *stream)
+                            void *stream, int ring_first = 0)
 {
     int rc = check_shape(sh, gated != 2);     // a compact store has no chunk grid over the raw buffer
     if (rc) return rc;
@@ -98,6 +98,7 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
         return KVEV_ERR_INVALID_ARG;
     if (gated && !compact && k_cap > 0 && sh->N_cap < 1) return KVEV_ERR_INVALID_ARG;
     if (causal != 0 && causal != 1) return KVEV_ERR_INVALID_ARG;
+    if (ring_first < 0 || (ring_first > 0 && ring_first >= sh->T_cap)) return KVEV_ERR_INVALID_ARG;
     if (Tq == 0) return KVEV_OK;
     if ((int64_t)sh->L * sh->B * sh->H * Tq > (int64_t)1 << 26) return KVEV_ERR_INVALID_ARG;
 
@@ -117,7 +118,7 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     a.S = sh->L * sh->B * kv_heads(sh); a.Tq = Tq; a.d = sh->d;
     a.G = sh->H / kv_heads(sh); a.Hkv = kv_heads(sh); a.causal = causal;
     a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = compact ? k_cap : sh->N_cap; a.k_cap = k_cap;
-    a.win0 = win0; a.gated = gated ? 1 : 0;
+    a.win0 = win0; a.ring_first = ring_first; a.gated = gated ? 1 : 0;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
     hipError_t e = mq ? launch_attn_mq(a, static_cast<hipStream_t>(stream))
@@ -280,10 +281,11 @@ int kvev_dense_attention(const kvev_shape *sh, const void *Q, int Tq, const void
 }
 
 int kvev_compact_attention(const kvev_shape *sh, const void *Q, int Tq, const void *Kw, const void *Vw,
-                           const void *Kc, const void *Vc, const int32_t *count, int k_cap, int causal, void *O,
-                           void *ws, size_t ws_bytes, void *stream)
+                           int win_first, const void *Kc, const void *Vc, const int32_t *count, int k_cap,
+                           int causal, void *O, void *ws, size_t ws_bytes, void *stream)
 {
-    return attention_common(sh, Q, Tq, Kw, Vw, Kc, Vc, nullptr, count, k_cap, 2, causal, O, ws, ws_bytes, stream);
+    return attention_common(sh, Q, Tq, Kw, Vw, Kc, Vc, nullptr, count, k_cap, 2, causal, O, ws, ws_bytes, stream,
+                            win_first);
 }
 
 int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, const void *Vbar_new,

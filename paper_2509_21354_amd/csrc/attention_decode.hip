@@ -103,7 +103,9 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
                 off = (seq_sum + c) * D;
                 kb = Kbar; vb = Vbar;
             } else {
-                off = (seq_raw + a.win0 + (j - cnt)) * D;
+                int r = a.win0 + (j - cnt) + a.ring_first;       // (ring_first is 0 unless the raw buffer is a ring)
+                r = r >= a.T_cap ? r - a.T_cap : r;
+                off = (seq_raw + r) * D;
                 kb = K; vb = V;
             }
             kr[u].load(kb + off + cl * EPL);

@@ -71,7 +71,9 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
         const int j = min((J0) + sr + RSTEP * i, nrows - 1);                                           \
         const bool sm = j < cnt;                                                                       \
         const int c_ = sm ? min(max(idx ? idx[j] : j, 0), a.N_cap - 1) : 0;                            \
-        const size_t off = (sm ? (seq_sum + c_) : (seq_raw + a.win0 + (j - cnt))) * D + dc * 8;        \
+        int r_ = a.win0 + (j - cnt) + a.ring_first;                                                    \
+        r_ = r_ >= a.T_cap ? r_ - a.T_cap : r_;                                                        \
+        const size_t off = (sm ? (seq_sum + c_) : (seq_raw + r_)) * D + dc * 8;                        \
         kreg[i] = *reinterpret_cast<const u32x4_t *>((sm ? Kbar : K) + off);                             \
         vreg[i] = *reinterpret_cast<const u32x4_t *>((sm ? Vbar : V) + off);                             \
     }
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
     // otherwise) are fetched through buffer descriptors: one lane offset for all loads, the tile and row
     // step in a scalar register; rows past the end read as zeros (they are masked in the softmax).
     const size_t raw_rows = (size_t)(a.T - a.win0);
-    const bool fast = raw_rows * D * sizeof(bf16_t) < ((size_t)1 << 32);
+    const bool fast = raw_rows * D * sizeof(bf16_t) < ((size_t)1 << 32) && a.ring_first == 0;   // (a ring wraps: no linear tile addresses)
     const __amdgpu_buffer_rsrc_t rk = make_rsrc(K + (seq_raw + a.win0) * D, (uint32_t)(raw_rows * D * sizeof(bf16_t)));
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(V + (seq_raw + a.win0) * D, (uint32_t)(raw_rows * D * sizeof(bf16_t)));
     const uint32_t voff = (uint32_t)((sr * D + dc * 8) * sizeof(bf16_t));

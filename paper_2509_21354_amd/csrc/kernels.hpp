@@ -17,6 +17,7 @@ struct AttnArgs {
     int causal;           // 1: the Tq queries are the last Tq cached tokens and see nothing after themselves
     int T, T_cap, N_cap, k_cap;
     int win0;             // first raw token attended (0 for the dense baseline)
+    int ring_first;       // compact form: the window buffer is a ring, its token t sits in row (ring_first + t) mod T_cap; else 0
     int gated;            // 1: kept summaries precede the raw rows
     int nsplit, rows_per_split;
     float scale_log2e;    // log2(e) / sqrt(d)

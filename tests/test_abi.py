@@ -129,12 +129,14 @@ def test_retain_and_compact_attention_validation():
     assert L.kvev_retain(r, 4, 32, None, FAKE, FAKE, 8, 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
     assert L.kvev_retain(r, 4, 32, FAKE, FAKE, FAKE, 8, 0, 4, None, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
     assert L.kvev_retain(r, 4, 32, FAKE, FAKE, FAKE, 8, -1, 4, FAKE, FAKE, FAKE, FAKE, FAKE, None) == kb.ERR_INVALID_ARG
-    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, None, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
-    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, None, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
-    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, -1, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, 0, None, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, None, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, FAKE, -1, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     big = _shape()                                                            # T = 4096 raw rows: split, needs scratch
     assert kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, big, 1, 32) > 0
-    assert L.kvev_compact_attention(ctypes.byref(big), FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_WORKSPACE
-    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 2, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # causal is 0 or 1
-    assert L.kvev_compact_attention(r, FAKE, 5000, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # frame longer than the window
+    assert L.kvev_compact_attention(ctypes.byref(big), FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_WORKSPACE
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 32, 2, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # causal is 0 or 1
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, -1, FAKE, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG  # ring start outside the buffer
+    assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, sh.T_cap, FAKE, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_compact_attention(r, FAKE, 5000, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 32, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # frame longer than the window
 

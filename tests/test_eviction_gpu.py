@@ -105,6 +105,21 @@ def test_compact_attention_gives_the_bits_of_the_indexed_attention(number, Tq):
     assert (_bits(O2) == _bits(O)).all()
     ref = orc.compact_attention(t["Q"], Kw.cpu(), Vw.cpu(), cfg.T - win0, Kc.cpu(), Vc.cpu(), cnt.cpu())
     assert_close_storage(O2, ref, cfg.dtype, "O (compact store)")
+    # the window buffer as a ring that wraps: same rows, rotated; same bits
+    wl, first = cfg.T - win0, W_cap - 3
+    rows = (first + torch.arange(wl, device="cuda")) % W_cap
+    Kr, Vr = torch.zeros_like(Kw), torch.zeros_like(Vw)
+    Kr[..., rows, :] = Kw[..., :wl, :]
+    Vr[..., rows, :] = Vw[..., :wl, :]
+    O5 = torch.empty_like(O)
+    kb.kvev_compact_attention(shw, g["Q"], Tq, Kr, Vr, Kc, Vc, cnt, k_cap, O5, ws, win_first=first)
+    torch.cuda.synchronize()
+    assert (_bits(O5) == _bits(O2)).all()
+    if Tq > 1:
+        kb.kvev_compact_attention(shw, g["Q"], Tq, Kr, Vr, Kc, Vc, cnt, k_cap, O5, ws, causal=1, win_first=first)
+        torch.cuda.synchronize()
+        ref_r = orc.compact_attention(t["Q"], Kr.cpu(), Vr.cpu(), wl, Kc.cpu(), Vc.cpu(), cnt.cpu(), causal=1, win_first=first)
+        assert_close_storage(O5, ref_r, cfg.dtype, "O (compact store, ring window, causal frame)")
     # a causal frame (the queries are the window's last Tq tokens): same bits as the indexed causal form, and the oracle's values
     if Tq > 1:
         O3, O4 = torch.empty_like(O), torch.empty_like(O)
@@ -138,6 +153,7 @@ def test_evicting_stream_equals_the_full_cache_stream():
     O1, O2 = torch.empty_like(g["Q"]), torch.empty_like(g["Q"])
     n_old, ncand_old = 0, 0
     resident_max = 0
+    wrapped = False
     for step in range(cfg.steps):
         T = (step + 1) * cfg.frame
         N, n_cand = T // cfg.C, max(0, T - cfg.W) // cfg.C
@@ -159,11 +175,15 @@ def test_evicting_stream_equals_the_full_cache_stream():
             un = full.util[..., ncand_old:n_cand].contiguous()
             kb.kvev_retain(sh, cfg.k, k_cap, Kn, Vn, un, n_in, ncand_old, n_in, Kc, Vc, ids, uc, cnt)
         win0 = n_cand * cfg.C
-        Kw[..., :T - win0, :] = g["K"][..., win0:T, :]                  # what a caller keeps of the raw cache
-        Vw[..., :T - win0, :] = g["V"][..., win0:T, :]
+        # what a caller keeps of the raw cache: a ring in which token p sits in row p mod W_cap; the frame is
+        # appended behind the last token, the window start just advances (no row moves)
+        rows = torch.arange(T - cfg.frame, T, device="cuda") % W_cap
+        Kw[..., rows, :] = g["K"][..., T - cfg.frame:T, :]
+        Vw[..., rows, :] = g["V"][..., T - cfg.frame:T, :]
+        wrapped = wrapped or (win0 % W_cap) + (T - win0) > W_cap
         shw = kb.make_shape(cfg, T=T - win0, T_cap=W_cap, N_cap=k_cap)
         ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, shw, 1, k_cap))
-        kb.kvev_compact_attention(shw, g["Q"], 1, Kw, Vw, Kc, Vc, cnt, k_cap, O2, ws)
+        kb.kvev_compact_attention(shw, g["Q"], 1, Kw, Vw, Kc, Vc, cnt, k_cap, O2, ws, win_first=win0 % W_cap)
         torch.cuda.synchronize()
         assert (cnt == full.count).all(), step
         m = int(cnt.max())
@@ -174,3 +194,4 @@ def test_evicting_stream_equals_the_full_cache_stream():
     ratio = cfg.T / (cfg.k + cfg.T - (max(0, cfg.T - cfg.W) // cfg.C) * cfg.C)
     print(f"\n[evicting stream] resident rows <= {resident_max} of {cfg.T} cached tokens; n/(W+M) = {ratio:.1f}")
     assert resident_max <= cfg.k + cfg.W + cfg.C
+    assert wrapped                      # the window did run across the end of its ring buffer
