@@ -460,6 +460,62 @@ def main():
                 "us_per_frame": round(t_frame, 2),
                 "decoded_tokens_per_s_per_layer": round(c4.B * c4.decode_per_step / (t_frame * 1e-6), 1),
                 "frames_per_s": round(1e6 / t_frame, 1)}
+            # the same stream with physical eviction: resident are the compact store (k rows), a ring of W + 2 frames
+            # raw rows and the summaries of chunks still inside the window; chunks that leave the window are merged
+            # into the store (no re-selection over all candidates), the decodes read store + ring
+            lead4 = (c4.L, c4.B, c4.H)
+            ring_cap = ((c4.W + c4.frame + c4.C + c4.frame - 1) // c4.frame + 1) * c4.frame
+            kc4 = c4.k
+            Kc4 = torch.zeros(lead4 + (kc4, c4.d), dtype=c4.torch_dtype, device=dev); Vc4 = torch.zeros_like(Kc4)
+            id4 = torch.full(lead4 + (kc4,), -1, dtype=torch.int32, device=dev)
+            uc4 = torch.zeros(lead4 + (kc4,), dtype=torch.float32, device=dev)
+            cn4 = torch.zeros(lead4, dtype=torch.int32, device=dev)
+            Kr4 = torch.zeros(lead4 + (ring_cap, c4.d), dtype=c4.torch_dtype, device=dev); Vr4 = torch.zeros_like(Kr4)
+            shr = kb.make_shape(c4, T=0, T_cap=ring_cap, N_cap=kc4)
+            shr.T = min(c4.W + c4.frame + c4.C, ring_cap)
+            wsr = kb.alloc_workspace(kb.workspace_bytes(kb.OP_COMPACT_ATTENTION, shr, 1, kc4), dev)
+
+            def frame_evict(si, done, ncand_old):
+                T4 = (si + 1) * c4.frame
+                sh4.T = T4
+                n4 = T4 // c4.C
+                r0 = (T4 - c4.frame) % ring_cap          # token p lives in ring row p mod ring_cap: a frame never wraps
+                Kr4[..., r0:r0 + c4.frame, :] = kv4["K"][..., T4 - c4.frame:T4, :]     # stands for the model's cache write
+                Vr4[..., r0:r0 + c4.frame, :] = kv4["V"][..., T4 - c4.frame:T4, :]
+                kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
+                kb.kvev_lstm_gate(sh4, s4.Kbar, s4.Vbar, lw4, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
+                ncand = max(0, T4 - c4.W) // c4.C
+                if ncand > ncand_old:
+                    kb.kvev_retain(sh4, c4.k, kc4, kb.RowsFrom(s4.Kbar, ncand_old, c4.d), kb.RowsFrom(s4.Vbar, ncand_old, c4.d),
+                                   kb.RowsFrom(s4.util, ncand_old, 1), s4.N_cap, ncand_old, ncand - ncand_old, Kc4, Vc4, id4, uc4, cn4)
+                win0 = ncand * c4.C
+                shr.T = T4 - win0
+                for j in range(c4.decode_per_step):
+                    kb.kvev_compact_attention(shr, q4[si, j], 1, Kr4, Vr4, Kc4, Vc4, cn4, kc4, O4, wsr, win_first=win0 % ring_cap)
+                return n4, ncand
+            O_ref = O4.clone()                           # last decode of the indexed stream (same queries)
+            for rep in range(2):
+                s4.h.zero_(); s4.c.zero_(); cn4.zero_()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                done, nc_old = 0, 0
+                for si in range(c4.steps):
+                    done, nc_old = frame_evict(si, done, nc_old)
+                e1.record()
+                torch.cuda.synchronize()
+            t_fe = e0.elapsed_time(e1) * 1e3 / c4.steps
+            rows4 = kc4 + ring_cap
+            out["streaming_cfg4_evicting"] = {
+                "us_per_frame": round(t_fe, 2),
+                "decoded_tokens_per_s_per_layer": round(c4.B * c4.decode_per_step / (t_fe * 1e-6), 1),
+                "resident_rows_per_sequence": rows4, "cached_tokens_at_the_end": c4.T,
+                "memory_ratio": round(c4.T / rows4, 2),
+                "last_output_equals_indexed_stream": bool((O4 == O_ref).all()),
+                "note": "per frame: the frame's K/V rows copied into the ring (stands for the model's cache write), "
+                        "pool + gate of its chunks, chunks leaving the window merged into the store, 8 decodes over "
+                        "store + ring; no re-selection"}
+            del Kc4, Vc4, Kr4, Vr4
             del kv4, s4, q4, O4
 
     # ---- large launch: config 3 attention, layer-batched (the bandwidth-bound regime) ----

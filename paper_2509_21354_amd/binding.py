@@ -90,9 +90,21 @@ def _check(status: int, what: str):
         raise KvevError(status, f"{what}: {msg}")
 
 
-def _ptr(t: Optional[torch.Tensor]):
+class RowsFrom:
+    """Rows r0 .. of the second-to-last (or, for a score array, last) axis of a contiguous tensor, passed as a
+    bare pointer: for entry points that take a row capacity of their own (kvev_retain's n_new_cap is then the
+    tensor's full row count), so that a range of rows needs no copy."""
+
+    def __init__(self, t: torch.Tensor, r0: int, row_elems: int):
+        assert t.is_contiguous(), "kvev takes contiguous tensors"
+        self.ptr = t.data_ptr() + r0 * row_elems * t.element_size()
+
+
+def _ptr(t):
     if t is None:
         return None
+    if isinstance(t, RowsFrom):
+        return ctypes.c_void_p(t.ptr)
     assert t.is_contiguous(), "kvev takes contiguous tensors"
     return ctypes.c_void_p(t.data_ptr())
 
