@@ -195,7 +195,10 @@ def main():
 
     mfma = cfg.dtype == "bf16"
     kernels = {"pool": "pool_mfma_kernel" if mfma and cfg.d_sum % 32 == 0 else "pool_generic_kernel",
-               "gate": f"lstm_rec_kernel<{cfg.d_g}>" if mfma and cfg.d_g in (64, 128, 256, 512) else "lstm_generic_kernel",
+               # one kvev_lstm_gate call = lstm_prep_kernel + lstm_inproj_kernel + lstm_rec_kernel per scratch block; the HIP
+               # events bracket the call, and the recurrence is 96 % of its kernel time at config 2 (profiles/)
+               "gate": (f"lstm_rec_kernel<{cfg.d_g}> (+ lstm_prep_kernel, lstm_inproj_kernel: the whole kvev_lstm_gate call)"
+                        if mfma and cfg.d_g in (64, 128, 256, 512) else "lstm_generic_kernel"),
                "select": "select_kernel",
                "attend": "attn_mq_kernel" if mfma and Tq >= 16 else "attn_decode_kernel",
                "dense": "attn_mq_kernel" if mfma and Tq >= 16 else "attn_decode_kernel"}
