@@ -81,8 +81,8 @@ def roof(name, kernel, cost, us, bound):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
     ap.add_argument("--sets", type=int, default=0, help="rotating input sets (0: enough to exceed 512 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
