@@ -178,6 +178,7 @@ def main():
         for j, (n, _) in enumerate(stages):
             stage_us[n] += row[j].elapsed_time(row[j + 1]) * 1e3 / args.steps
     gpu_ms = marks[0][0].elapsed_time(marks[-1][-1]) / args.steps
+    per_step_us = sorted(row[0].elapsed_time(row[-1]) * 1e3 for row in marks)      # spread over the timed steps
     ms_per_step = max(gpu_ms, wall_ms)       # host launch overhead counts when it is the limit
     value = cfg.B * Tq * cfg.L / (ms_per_step * 1e-3)
 
@@ -217,6 +218,8 @@ def main():
                    "rotating_input_sets": R},
         "stage_us": {k: round(v, 3) for k, v in stage_us.items()},
         "gpu_ms_per_step": round(gpu_ms, 5), "host_wall_ms_per_step": round(wall_ms, 5),
+        "step_us_median": round(per_step_us[len(per_step_us) // 2], 3), "step_us_min": round(per_step_us[0], 3),
+        "step_us_max": round(per_step_us[-1], 3),
     }
     if rooflines:
         dom = max(rooflines, key=lambda r: r["us_per_launch"])
