@@ -183,8 +183,10 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             bias[r] = bf16_to_f32(b_ih[row0 + 4 * g4 + r]) + bf16_to_f32(b_hh[row0 + 4 * g4 + r]);
-#pragma unroll 1
-        for (int j = 0; j < TT; ++j) {           // (a real loop: unrolled, the rows' fragments fill the register file; by two it measured 4 % slower)
+        // (a real loop for the long tiles: unrolled, the rows' fragments fill the register file, and by two it measured
+        // 4 % slower; the two-step tiles of small launches are faster unrolled)
+#pragma unroll TT <= 2 ? 2 : 1
+        for (int j = 0; j < TT; ++j) {
             f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
