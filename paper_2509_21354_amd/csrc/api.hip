@@ -135,20 +135,28 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
     return sh->dtype == KVEV_BF16 && (sh->d_g == 64 || sh->d_g == 128 || sh->d_g == 256 || sh->d_g == 512);
 }
 
-// W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch.
+static long long lstm_groups(const kvev_shape *sh)
+{
+    return (long long)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
+}
+
+// W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch:
+// packed W_hh and W_ih (2 bytes per element), then 32 words per layer (partial maxima of |W_hh|), padded to 256 bytes
+static size_t lstm_ws_weights(const kvev_shape *sh)
+{
+    return (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 + ((size_t)sh->L * 32 * 4 + 255) / 256 * 256;
+}
+
+// ... followed by the exchange slots of the paired recurrence, where it applies.
 static size_t lstm_ws_pack(const kvev_shape *sh)
 {
-    // packed W_hh and W_ih (2 bytes per element), then 32 words per layer (partial maxima of |W_hh|), padded to 256 bytes
-    return lstm_takes_mfma(sh) ? (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 +
-                                     ((size_t)sh->L * 32 * 4 + 255) / 256 * 256
-                               : 0;
+    return lstm_takes_mfma(sh) ? lstm_ws_weights(sh) + lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh)) : 0;
 }
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
 {
     if (!lstm_takes_mfma(sh)) return 0;
-    const size_t groups = (size_t)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
-    return groups * 16 * 4 * sh->d_g * sizeof(float);
+    return (size_t)lstm_groups(sh) * 16 * 4 * sh->d_g * sizeof(float);
 }
 
 }  // namespace kvev
@@ -235,6 +243,8 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         a.wih_packed = a.whh_packed + (size_t)sh->L * 4 * sh->d_g * sh->d_g / 8;
         a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) +
                                                 (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
+        a.exch_bytes = lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh));
+        a.exch = a.exch_bytes ? static_cast<unsigned char *>(ws) + lstm_ws_weights(sh) : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
     } else {

@@ -40,10 +40,20 @@ struct LstmArgs {
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *whh_packed;   // workspace: W_hh in fragment order (16-byte pieces; fp16 inside)
     uint32_t *whh_max_bits;   // workspace: 32 partial maxima of |W_hh| per layer as bit patterns (their maximum fixes the power-of-two scale)
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *wih_packed;   // workspace: W_ih in fragment order
+    unsigned char *exch;  // workspace: exchange slots of the paired recurrence (lstm_pair_exch_bytes), or null
+    size_t exch_bytes;    // 0: one workgroup per sequence group
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block
 };
+
+// The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch is
+// small enough for all of them to be resident together (bounded waits in the kernel cover the rest); the
+// exchange needs 64 KiB of scratch per group.  0: not paired.
+inline size_t lstm_pair_exch_bytes(int d_g, long long groups)
+{
+    return d_g == 256 && groups <= 64 ? (size_t)groups * 65536 : 0;
+}
 
 struct SelectArgs {
     const float *util, *gate;

@@ -137,6 +137,11 @@ template <int DG, int D, int TT>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb, int ny_proj)
 {
     constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT, XP = 2 * D + 8, THREADS = Geo<DG>::THREADS;
+    if (a.exch_bytes) {      // the paired recurrence that follows starts from cleared exchange slots
+        const size_t nthreads = (size_t)gridDim.x * gridDim.y * THREADS;
+        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * THREADS + threadIdx.x; i * 16 < a.exch_bytes; i += nthreads)
+            reinterpret_cast<uint4 *>(a.exch)[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
     if ((int)blockIdx.y >= ny_proj) {
         pack_whh_blocks<DG>(a, ((int)blockIdx.y - ny_proj) * gridDim.x + blockIdx.x, ((int)gridDim.y - ny_proj) * gridDim.x);
         return;
@@ -494,6 +499,266 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
     }
 }
 
+// ---- the recurrence of a 16-sequence group on a pair of compute units ----------------------------------------
+// With few sequences (config 2: 32) the chip is empty and the step time of the kernel above is what one CU can do:
+// 1.7 us of MFMA, and a weight stream out of L2 on top.  Here two workgroups share a group: each owns half of the
+// hidden units (8 waves x 16 units, all four gates), so its half of W_hh (256 KiB as fp16) sits in registers for the
+// whole launch, and a step is half the matrix work per CU.  What the halves owe each other every step is the new h
+// of the other half, 16 x 128 values as (hi, lo) fp16 terms.
+//
+// Exchange: a wave publishes its 16 units x 16 sequences as two 16-byte stores per lane of the form
+// {payload, stamp, payload, stamp} (stamp = step + 1 within the launch) with device scope, into a slot of its own;
+// the same wave of the partner polls that slot until all four stamps of its two loads carry the step it waits for.
+// Data and stamp share an aligned 8-byte word, which a store writes and a load reads as one, so no flag, fence or
+// ordering between different addresses is involved.  Two slots by step parity: a slot is rewritten two steps
+// later, which the writer can only reach after the partner has consumed it (it needs the partner's next h, published
+// after that read).  The input projection's launch clears the slots before every launch of this kernel, so a stamp
+// can only come from the current one.
+//
+// The products over the workgroup's own half of h do not need the exchange and run while it is in flight:
+//   own-half MFMAs | take partner's h, stage in LDS | barrier | partner-half MFMAs | cell, publish | barrier.
+// The utility logit w_s . h_t + b_s is completed one step later, when the partner's half has arrived (as hi + lo,
+// 22 bits); one wave of member 0 writes it while it would otherwise wait at the step's last barrier.
+// Measured at config 2 (32 sequences, 4 workgroups): 2.3 us per step against 3.1 us for one workgroup per group;
+// the exchange is mostly hidden (the first look finds the data 60-90 % of the time), and what is left is a SIMD's
+// own serial work: 0.87 us of MFMA and 0.7 us of gate nonlinearities (quarter-rate exp2 and rcp) for its two
+// waves, plus two barriers and the LDS latency in front of each run of MFMAs.
+//
+// Every wait is bounded: a wave that does not see its partner's data within kPairSpinLimit polls raises a flag in
+// LDS, the workgroup leaves the step loop together after the next barrier and marks the launch's scores as NaN.
+// The launch must be co-resident (at most one workgroup per CU is asked for: 2 x groups <= 128 workgroups).
+constexpr int kPairSpinLimit = 1 << 22;
+constexpr uint32_t kPairSlotBytes = 2 * 64 * 16;                       // one wave's publication: 2 lines x 64 lanes x 16 B
+constexpr uint32_t kPairExchBytes = 2 * 2 * 8 * kPairSlotBytes;        // [parity][member][wave] per sequence group
+
+__device__ __forceinline__ void lds_barrier()
+{
+    // LDS traffic of this wave done, then the barrier: unlike __syncthreads() this does not wait for the global
+    // stores in flight (the publication), which nobody in the workgroup reads
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int DG>
+__global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, int nb)
+{
+    static_assert(DG == 256, "8 waves x 16 units x 2 workgroups");
+    using G = Geo<DG>;                     // the packed operands keep the single-workgroup kernel's geometry
+    constexpr int NW = 8, KS = DG / 32, KH = KS / 2, HP = DG + 8;
+    typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+    __shared__ __align__(16) f16_t s_h[2 * 2 * 16 * HP];         // [buffer][hi, lo][sequence][unit]
+    __shared__ float s_up[2][NW][64], s_up2[NW][64];          // per-lane shares of the utility logit: own units (by step parity), partner's units
+    __shared__ int s_fail;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g4 = lane >> 4;
+    const int member = blockIdx.x & 1, gid = blockIdx.x >> 1;
+    const int gpl = (a.BH + 15) / 16;
+    const int l = gid / gpl, grp = gid % gpl;
+    const bool live = grp * 16 + n < a.BH;
+    const size_t s = (size_t)l * a.BH + min(grp * 16 + n, a.BH - 1);
+    const int tile = member * NW + wave, ptile = (1 - member) * NW + wave;      // unit tiles of this wave and of its partner wave
+    const int ks_own = member * KH, ks_par = (1 - member) * KH;
+
+    const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
+    const float b_s = bf16_to_f32(static_cast<const bf16_t *>(a.b_s)[l]);
+    const float inv_scale = ldexpf(1.f, -whh_scale_exp(whh_layer_max(a.whh_max_bits, l)));
+    if (tid == 0) s_fail = 0;
+
+    const uint32_t lane16 = lane * 16;
+    // the tile's weights: items [ks] of (packed wave tile / 2, unit tile tile % 2), own-half k-steps first
+    const unsigned char *wbase = reinterpret_cast<const unsigned char *>(
+        a.whh_packed + (((size_t)l * G::NW + (tile >> 1)) * G::ITEMS + (tile & 1) * KS) * 4 * 64);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wbase, KS * 4096);
+    f16x8_t wreg[KS][4];
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wreg[j][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, (uint32_t)((j < KH ? ks_own + j : ks_par + j - KH) * 4096));
+    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
+        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(gid, a.tb, 0, tile >> 1, tile & 1, 0) * 64);
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * G::NW * G::UT * 4096 - (uint32_t)tile * 4096);
+    const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)gid * kPairExchBytes, kPairExchBytes);
+
+    float c_reg[4], ws_own[4], ws_par[4];
+    f16_t *h_own = s_h + (size_t)n * HP + tile * 16 + 4 * g4;       // + (buf*2 + plane)*16*HP
+    f16_t *h_par = s_h + (size_t)n * HP + ptile * 16 + 4 * g4;
+    const f16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;               // + (buf*2 + plane)*16*HP + ks*32
+    auto split = [](const float (&hv)[4], f16x4_t &hi, f16x4_t &lo) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            hi[r] = (f16_t)hv[r];
+            lo[r] = (f16_t)(hv[r] - (float)hi[r]);
+        }
+    };
+    {   // h of step t0 - 1, both halves, from the fp32 state
+        float ho[4], hp[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            c_reg[r] = live ? a.c[s * DG + tile * 16 + 4 * g4 + r] : 0.f;
+            ho[r] = live ? a.h[s * DG + tile * 16 + 4 * g4 + r] : 0.f;
+            hp[r] = live ? a.h[s * DG + ptile * 16 + 4 * g4 + r] : 0.f;
+            ws_own[r] = bf16_to_f32(w_s[tile * 16 + 4 * g4 + r]);
+            ws_par[r] = bf16_to_f32(w_s[ptile * 16 + 4 * g4 + r]);
+        }
+        f16x4_t hi, lo;
+        split(ho, hi, lo);
+        *reinterpret_cast<f16x4_t *>(h_own) = hi;
+        *reinterpret_cast<f16x4_t *>(h_own + 16 * HP) = lo;
+        split(hp, hi, lo);
+        *reinterpret_cast<f16x4_t *>(h_par) = hi;
+        *reinterpret_cast<f16x4_t *>(h_par + 16 * HP) = lo;
+    }
+    __syncthreads();
+
+    // one look at the partner wave's slot `par` (two device-scope loads; their results are examined later)
+    auto ask = [&](int par, u32x4_t &r0, u32x4_t &r1) __attribute__((always_inline)) {
+        const uint32_t off = (uint32_t)((par * 2 + (1 - member)) * NW + wave) * kPairSlotBytes;
+        r0 = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, (int)lane16, (int)off, 16);           // device scope
+        r1 = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, (int)lane16, (int)(off + 1024), 16);
+    };
+    // The partner wave's h of the step stamped `stamp`, from slot `par`: staged in LDS buffer `buf`, and its share of
+    // the utility logit left in s_up2.  (ra, r: two looks at the slot asked for earlier, so that their round trips,
+    // about 1 us behind the stores of the publication, run behind the own-half MFMAs; more looks follow if neither
+    // carries the stamp yet.)
+    auto receive = [&](int par, uint32_t stamp, int buf, u32x4_t ra0, u32x4_t ra1, u32x4_t r0, u32x4_t r1) __attribute__((always_inline)) {
+        auto all_in = [&](const u32x4_t &x0, const u32x4_t &x1) __attribute__((always_inline)) {
+            const bool ok = x0[1] == stamp && x0[3] == stamp && x1[1] == stamp && x1[3] == stamp;
+            return __all(ok) != 0;
+        };
+        bool got = all_in(ra0, ra1);
+        if (got) { r0 = ra0; r1 = ra1; }
+        for (int spin = 0; !got && spin < kPairSpinLimit; ++spin) {
+            asm volatile("" ::: "memory");
+            if (all_in(r0, r1)) { got = true; break; }
+            if ((spin & 255) == 255 && s_fail) break;
+            ask(par, r0, r1);
+        }
+        if (!got) s_fail = 1;
+        const uint2 hi2 = make_uint2(r0[0], r0[2]), lo2 = make_uint2(r1[0], r1[2]);
+        const f16x4_t hi = __builtin_bit_cast(f16x4_t, hi2), lo = __builtin_bit_cast(f16x4_t, lo2);
+        *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 0) * 16 * HP) = hi;
+        *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 1) * 16 * HP) = lo;
+        float up = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) up = fmaf(ws_par[r], (float)hi[r] + (float)lo[r], up);
+        s_up2[wave][lane] = up;
+    };
+    // Member 0 completes the logit of a step once both halves are in: own shares (buffer `ub`), then the partner's.
+    // One wave does it, at a point where it would otherwise wait at the barrier for the slower ones.
+    auto write_util = [&](int ub, int step) __attribute__((always_inline)) {
+        if (member == 0 && wave == 0) {
+            float u = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) u += s_up[ub][w][lane];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) u += s_up2[w][lane];
+            u += __shfl_xor(u, 16);
+            u += __shfl_xor(u, 32);
+            u += b_s;
+            if (live && g4 == 0) {
+                a.util[s * a.N_cap + t0 + step] = u;
+                a.gate[s * a.N_cap + t0 + step] = sigmoid_hw(u);
+            }
+        }
+    };
+    // NK k-steps from ks0 on, with the weight fragments [j0, j0 + NK)
+    auto mfma_run = [&](f32x4_t (&acc)[4], int buf, int ks0, auto jbase, auto nk) __attribute__((always_inline)) {
+        constexpr int j0 = decltype(jbase)::value, NK = decltype(nk)::value;
+        f16x8_t hb[NK][2];
+#pragma unroll
+        for (int j = 0; j < NK; ++j)
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+                hb[j][p] = *reinterpret_cast<const f16x8_t *>(h_rd + (size_t)(buf * 2 + p) * 16 * HP + (ks0 + j) * 32);
+#pragma unroll
+        for (int j = 0; j < NK; ++j)
+#pragma unroll
+            for (int p = 1; p >= 0; --p)          // the small term first
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wreg[j0 + j][q], hb[j][p], acc[q], 0, 0, 0);
+    };
+    using std::integral_constant;
+
+    bool failed = false;
+    u32x4_t ra0 = {0, 0, 0, 0}, ra1 = {0, 0, 0, 0};
+    for (int tt = 0; tt < nb; ++tt) {
+        const int cur = tt & 1, nxt = cur ^ 1;
+        f32x4_t acc[4], xin[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            xin[q] = buffer_load16_nt<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)tt * G::NW * G::UT * 4096);
+            acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        // the partner published h of step tt - 1 at the end of that step (slot nxt, stamp tt); a first look at the slot
+        // went out right after this workgroup's own publication, a second one goes now
+        u32x4_t rb0 = {0, 0, 0, 0}, rb1 = {0, 0, 0, 0};
+        if (tt > 0) ask(nxt, rb0, rb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_run(acc, cur, ks_own, integral_constant<int, 0>{}, integral_constant<int, KH>{});
+        if (tt > 0) {
+            receive(nxt, (uint32_t)tt, cur, ra0, ra1, rb0, rb1);
+            lds_barrier();
+            if (s_fail) { failed = true; break; }
+        }
+        mfma_run(acc, cur, ks_par, integral_constant<int, KH>{}, integral_constant<int, KH>{});
+
+        float hv[4], upart = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float ig = sigmoid_hw(fmaf(acc[0][r], inv_scale, xin[0][r]));
+            const float fg = sigmoid_hw(fmaf(acc[1][r], inv_scale, xin[1][r]));
+            const float gg = tanh_hw(fmaf(acc[2][r], inv_scale, xin[2][r]));
+            const float og = sigmoid_hw(fmaf(acc[3][r], inv_scale, xin[3][r]));
+            const float cn = fmaf(fg, c_reg[r], ig * gg);
+            c_reg[r] = cn;
+            float hn = og * tanh_hw(cn);
+            asm volatile("" : "+v"(hn));
+            hv[r] = hn;
+            upart = fmaf(ws_own[r], hn, upart);
+        }
+        f16x4_t hi, lo;
+        split(hv, hi, lo);
+        {   // to the partner first (the long way), then to this workgroup's own waves
+            const uint2 hi2 = __builtin_bit_cast(uint2, hi), lo2 = __builtin_bit_cast(uint2, lo);
+            const uint32_t stamp = (uint32_t)tt + 1;
+            const uint32_t off = (uint32_t)((cur * 2 + member) * NW + wave) * kPairSlotBytes;
+            const u32x4_t l0 = {hi2.x, stamp, hi2.y, stamp}, l1 = {lo2.x, stamp, lo2.y, stamp};
+            __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
+            __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
+        }
+        ask(cur, ra0, ra1);          // the partner is about to publish the same step
+        *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 0) * 16 * HP) = hi;
+        *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 1) * 16 * HP) = lo;
+        s_up[cur][wave][lane] = upart;
+        if (tt == nb - 1 && live)
+            *reinterpret_cast<float4 *>(a.h + s * DG + tile * 16 + 4 * g4) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        if (tt > 0) write_util(nxt, tt - 1);       // both halves of step tt - 1 have been in LDS since this step's first barrier
+        lds_barrier();
+    }
+    if (!failed) {      // the last step's logit needs the partner's last h
+        u32x4_t r0, r1;
+        ask((nb - 1) & 1, r0, r1);
+        receive((nb - 1) & 1, (uint32_t)nb, nb & 1, ra0, ra1, r0, r1);
+        lds_barrier();
+        failed = s_fail != 0;
+        if (!failed) write_util((nb - 1) & 1, nb - 1);
+    }
+    if (live) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) a.c[s * DG + tile * 16 + 4 * g4 + r] = failed ? __builtin_nanf("") : c_reg[r];
+    }
+    if (failed && tid < 16 && live) {
+        for (int t = 0; t < nb; ++t) {
+            a.util[s * a.N_cap + t0 + t] = __builtin_nanf("");
+            a.gate[s * a.N_cap + t0 + t] = __builtin_nanf("");
+        }
+    }
+}
+
 template <int DG>
 static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
 {
@@ -544,6 +809,12 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         } else {
             if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
             else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
+        }
+        if constexpr (DG == 256) {
+            if (a.exch_bytes) {
+                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), 0, st, a, t0, nb);
+                continue;
+            }
         }
         hipLaunchKernelGGL((lstm_rec_kernel<DG>), dim3(groups), dim3(Geo<DG>::THREADS), lds, st, a, t0, nb);
     }

@@ -204,6 +204,9 @@ LSTM_CASES = [
     _cfg(145, "bf16", d=128, T=320, C=32, d_g=40),                        # d_g the MFMA tiling does not take
     _cfg(146, "bf16", d=128, T=768, C=32, d_g=512, L=1, B=1, H=3),        # widest gate: unit tiles one after the other
     _cfg(147, "bf16", d=64, T=576, C=16, d_g=128, L=2, B=2, H=9),         # W_hh fully resident on chip
+    _cfg(148, "bf16", d=128, T=800, C=32, d_g=256, L=1, B=2, H=24),       # 3 full groups, each on a pair of workgroups
+    _cfg(149, "bf16", d=64, T=192, C=32, d_g=256, L=4, B=4, H=64),        # 64 groups: the largest paired launch
+    _cfg(150, "bf16", d=64, T=192, C=32, d_g=256, L=13, B=5, H=16),       # 65 groups: one workgroup per group again
 ]
 
 
