@@ -109,6 +109,12 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  * Needs 0 <= chunk_begin <= chunk_end <= N_cap.  Workspace: see
  * kvev_workspace_bytes (fp32 input projections of a block of steps); any size
  * from one step's worth up is accepted, smaller blocks mean more launches.
+ * Calls that share a workspace must not overlap (it also carries what the
+ * workgroups of one launch exchange).  Small launches (bf16, d_g = 256, at
+ * most 64 groups of 16 sequences) run each group on two cooperating
+ * workgroups, which wait for each other's data with a bounded number of polls;
+ * should the bound ever expire (the GPU held by other work for seconds), the
+ * launch ends normally and its util, gate and c entries are NaN.
  * Errors: INVALID_ARG, UNSUPPORTED as above; WORKSPACE if ws is too small. */
 int kvev_lstm_gate(const kvev_shape *shape, const void *Kbar, const void *Vbar,
                    const kvev_lstm_w *w, int chunk_begin, int chunk_end, float *h, float *c,
