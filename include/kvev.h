@@ -204,6 +204,16 @@ int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const
  * arguments are invalid. */
 size_t kvev_workspace_bytes(int op, const kvev_shape *shape, int n, int k_cap);
 
+/* For tests of the gate's failure path, not for production use.  Small launches
+ * of kvev_lstm_gate run a group of sequences on two workgroups that wait for
+ * each other's data (see there).  This sets, for later calls in this process,
+ * the number of polls one such wait may take (default 1 << 22) and the member
+ * (0 or 1; -1 = none, the default) that withholds what it would publish, so
+ * that its partner's wait expires: every kernel still ends normally and the
+ * affected launch's util, gate and c come back NaN.  Not thread-safe.
+ * Errors: INVALID_ARG for spin_limit < 1 or a member outside -1..1. */
+int kvev_debug_pair_wait(int spin_limit, int mute_member);
+
 /* Static description of a status code. */
 const char *kvev_status_string(int status);
 

@@ -26,7 +26,7 @@ OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, 
 
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
            "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
-           "kvev_status_string", "kvev_last_hip_error", "kvev_version")
+           "kvev_status_string", "kvev_last_hip_error", "kvev_version", "kvev_debug_pair_wait")
 
 
 class Shape(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_workspace_bytes.argtypes = [ci, shp, ci, ci]
         L.kvev_workspace_bytes.restype = sz
+        L.kvev_debug_pair_wait.argtypes = [ci, ci]
+        L.kvev_debug_pair_wait.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
@@ -122,6 +124,10 @@ def make_shape(cfg=None, **kw) -> Shape:
                  H_kv=getattr(cfg, "H_kv", 0))
     v.update(kw)
     return Shape(**v)
+
+
+def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> None:
+    _check(lib().kvev_debug_pair_wait(spin_limit, mute_member), "kvev_debug_pair_wait")
 
 
 def workspace_bytes(op: int, shape: Shape, n: int, k_cap: int = 0) -> int:

@@ -135,6 +135,10 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
     return sh->dtype == KVEV_BF16 && (sh->d_g == 64 || sh->d_g == 128 || sh->d_g == 256 || sh->d_g == 512);
 }
 
+// Bound on the polls of one wait of the paired recurrence (each poll is a round trip to memory, about a
+// microsecond: seconds in all), and the member whose publications are withheld; kvev_debug_pair_wait changes them.
+static int g_pair_spin_limit = 1 << 22, g_pair_mute = -1;
+
 static long long lstm_groups(const kvev_shape *sh)
 {
     return (long long)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
@@ -244,6 +248,8 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) +
                                                 (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
         a.exch_bytes = lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh));
+        a.pair_spin_limit = g_pair_spin_limit;
+        a.pair_mute = g_pair_mute;
         a.exch = a.exch_bytes ? static_cast<unsigned char *>(ws) + lstm_ws_weights(sh) : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
@@ -317,6 +323,14 @@ int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, co
     a.k = k; a.k_cap = k_cap; a.n_new_cap = n_new_cap; a.first_chunk = first_chunk; a.n_new = n_new;
     hipError_t e = launch_retain(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_debug_pair_wait(int spin_limit, int mute_member)
+{
+    if (spin_limit < 1 || mute_member < -1 || mute_member > 1) return KVEV_ERR_INVALID_ARG;
+    g_pair_spin_limit = spin_limit;
+    g_pair_mute = mute_member;
+    return KVEV_OK;
 }
 
 size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)

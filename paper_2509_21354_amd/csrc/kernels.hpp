@@ -42,6 +42,8 @@ struct LstmArgs {
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *wih_packed;   // workspace: W_ih in fragment order
     unsigned char *exch;  // workspace: exchange slots of the paired recurrence (lstm_pair_exch_bytes), or null
     size_t exch_bytes;    // 0: one workgroup per sequence group
+    int pair_spin_limit;  // polls a wave of the paired recurrence spends on one wait before it gives up
+    int pair_mute;        // member (0, 1) whose publications are withheld, -1: none (failure-path tests only)
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block

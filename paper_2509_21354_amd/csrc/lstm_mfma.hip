@@ -524,10 +524,9 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 // own serial work: 0.87 us of MFMA and 0.7 us of gate nonlinearities (quarter-rate exp2 and rcp) for its two
 // waves, plus two barriers and the LDS latency in front of each run of MFMAs.
 //
-// Every wait is bounded: a wave that does not see its partner's data within kPairSpinLimit polls raises a flag in
+// Every wait is bounded: a wave that does not see its partner's data within a.pair_spin_limit polls raises a flag in
 // LDS, the workgroup leaves the step loop together after the next barrier and marks the launch's scores as NaN.
 // The launch must be co-resident (at most one workgroup per CU is asked for: 2 x groups <= 128 workgroups).
-constexpr int kPairSpinLimit = 1 << 22;
 constexpr uint32_t kPairSlotBytes = 2 * 64 * 16;                       // one wave's publication: 2 lines x 64 lanes x 16 B
 constexpr uint32_t kPairExchBytes = 2 * 2 * 8 * kPairSlotBytes;        // [parity][member][wave] per sequence group
 
@@ -630,7 +629,7 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
         };
         bool got = all_in(ra0, ra1);
         if (got) { r0 = ra0; r1 = ra1; }
-        for (int spin = 0; !got && spin < kPairSpinLimit; ++spin) {
+        for (int spin = 0; !got && spin < a.pair_spin_limit; ++spin) {
             asm volatile("" ::: "memory");
             if (all_in(r0, r1)) { got = true; break; }
             if ((spin & 255) == 255 && s_fail) break;
@@ -727,8 +726,10 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
             const uint32_t stamp = (uint32_t)tt + 1;
             const uint32_t off = (uint32_t)((cur * 2 + member) * NW + wave) * kPairSlotBytes;
             const u32x4_t l0 = {hi2.x, stamp, hi2.y, stamp}, l1 = {lo2.x, stamp, lo2.y, stamp};
-            __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
-            __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
+            if (member != a.pair_mute) {
+                __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
+                __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
+            }
         }
         ask(cur, ra0, ra1);          // the partner is about to publish the same step
         *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 0) * 16 * HP) = hi;

@@ -29,6 +29,14 @@ def test_library_exports_every_declared_symbol():
     assert b"workspace" in L.kvev_status_string(kb.ERR_WORKSPACE)
 
 
+def test_debug_pair_wait_validation():
+    L = kb.lib()
+    assert L.kvev_debug_pair_wait(0, -1) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, 2) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, -2) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(1 << 22, -1) == kb.OK      # the defaults
+
+
 FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
 
 

@@ -249,6 +249,42 @@ def test_lstm_gate(cfg):
     assert (util[..., N:] == 9.0).all() and (gate[..., N:] == 9.0).all()
 
 
+def test_lstm_pair_wait_expires_cleanly():
+    """The paired recurrence (d_g = 256, few groups) with one member's publications withheld and a tiny bound on
+    the polls: both workgroups give up, every kernel ends normally, the launch's scores and cell state are NaN,
+    and the next call (defaults restored) is unaffected."""
+    cfg = _cfg(151, "bf16", d=64, T=320, C=32, d_g=256, L=1, B=1, H=5)
+    N = cfg.T // cfg.C
+    w = synth.make_weights(cfg, "cpu")
+    Kbar, Vbar = _summaries(cfg, N)
+    sh = kb.make_shape(cfg, N_cap=N)
+    lead = (cfg.L, cfg.B, cfg.H)
+    gw = dev(w)
+    ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+    Kb, Vb = Kbar.cuda(), Vbar.cuda()
+
+    def run():
+        h = torch.zeros(lead + (cfg.d_g,), device="cuda")
+        c = torch.zeros_like(h)
+        util = torch.full(lead + (N,), 9.0, device="cuda")
+        gate = torch.full_like(util, 9.0)
+        kb.kvev_lstm_gate(sh, Kb, Vb, kb.lstm_weights(gw), 0, N, h, c, util, gate, ws)
+        torch.cuda.synchronize()
+        return h, c, util, gate
+
+    for mute in (1, 0):
+        kb.kvev_debug_pair_wait(64, mute)
+        try:
+            h, c, util, gate = run()
+        finally:
+            kb.kvev_debug_pair_wait()
+        assert torch.isnan(util).all() and torch.isnan(gate).all() and torch.isnan(c).all()
+    h, c, util, gate = run()
+    rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
+    assert np.abs(util.cpu().numpy() - ru).max() <= SCORE_TOL
+    assert np.abs(c.cpu().numpy() - rc).max() <= 2 * SCORE_TOL
+
+
 def _run_cold(cfg, t, g):
     st = kb.DecodeState(cfg)
     O = torch.empty_like(g["Q"])
