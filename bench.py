@@ -80,7 +80,8 @@ def roof(name, kernel, cost, us, bound):
 
 def rec_kernel_name(cfg):
     groups = cfg.L * ((cfg.B * cfg.H + 15) // 16)
-    return f"lstm_rec_pair_kernel<{cfg.d_g}>" if cfg.d_g == 256 and groups <= 64 else f"lstm_rec_kernel<{cfg.d_g}>"
+    paired = (cfg.d_g == 256 and groups <= 64) or (cfg.d_g == 512 and groups <= 128)
+    return f"lstm_rec_pair_kernel<{cfg.d_g}>" if paired else f"lstm_rec_kernel<{cfg.d_g}>"
 
 
 def main():
@@ -203,7 +204,7 @@ def main():
     kernels = {"pool": "pool_mfma_kernel" if mfma and cfg.d_sum % 32 == 0 else "pool_generic_kernel",
                # one kvev_lstm_gate call = lstm_prep_kernel + lstm_inproj_kernel + the recurrence per scratch block; the HIP
                # events bracket the call, and the recurrence is 95 % of its kernel time at config 2 (profiles/).  Up to 64
-               # sequence groups of d_g = 256 run the recurrence on pairs of workgroups (lstm_rec_pair_kernel).
+               # sequence groups of d_g = 256 (128 of d_g = 512) run the recurrence on pairs of workgroups (lstm_rec_pair_kernel).
                "gate": (f"{rec_kernel_name(cfg)} (+ lstm_prep_kernel, lstm_inproj_kernel: the whole kvev_lstm_gate call)"
                         if mfma and cfg.d_g in (64, 128, 256, 512) else "lstm_generic_kernel"),
                "select": "select_kernel",

@@ -50,11 +50,15 @@ struct LstmArgs {
 };
 
 // The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch is
-// small enough for all of them to be resident together (bounded waits in the kernel cover the rest); the
-// exchange needs 64 KiB of scratch per group.  0: not paired.
+// small enough for all of them to be resident together (bounded waits in the kernel cover the rest): up to 64 groups
+// at d_g = 256, up to 128 (one workgroup per compute unit) at d_g = 512, where a single workgroup is bound by
+// the weight stream out of L2 and a pair halves it.  The exchange needs 64 KiB of scratch per group and 256
+// hidden units.  0: not paired.
 inline size_t lstm_pair_exch_bytes(int d_g, long long groups)
 {
-    return d_g == 256 && groups <= 64 ? (size_t)groups * 65536 : 0;
+    if (d_g == 256 && groups <= 64) return (size_t)groups * 65536;
+    if (d_g == 512 && groups <= 128) return (size_t)groups * 131072;
+    return 0;
 }
 
 struct SelectArgs {

@@ -501,14 +501,16 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 
 // ---- the recurrence of a 16-sequence group on a pair of compute units ----------------------------------------
 // With few sequences (config 2: 32) the chip is empty and the step time of the kernel above is what one CU can do:
-// 1.7 us of MFMA, and a weight stream out of L2 on top.  Here two workgroups share a group: each owns half of the
-// hidden units (8 waves x 16 units, all four gates), so its half of W_hh (256 KiB as fp16) sits in registers for the
-// whole launch, and a step is half the matrix work per CU.  What the halves owe each other every step is the new h
-// of the other half, 16 x 128 values as (hi, lo) fp16 terms.
+// at d_g = 256, 1.7 us of MFMA and a weight stream out of L2 on top; at d_g = 512 (config 5: 128 groups on 256 CUs)
+// 13.7 us for the 2 MiB of W_hh that a CU pulls out of L2 every step.  Here two workgroups share a group: each owns
+// half of the hidden units (8 waves x 16 or 32 units, all four gates), so a step is half the matrix work, half the
+// gate nonlinearities and half the weight bytes per CU; at d_g = 256 its half of W_hh (256 KiB as fp16) sits in
+// registers for the whole launch.  What the halves owe each other every step is the new h of the other half,
+// 16 x d_g/2 values as (hi, lo) fp16 terms.
 //
-// Exchange: a wave publishes its 16 units x 16 sequences as two 16-byte stores per lane of the form
-// {payload, stamp, payload, stamp} (stamp = step + 1 within the launch) with device scope, into a slot of its own;
-// the same wave of the partner polls that slot until all four stamps of its two loads carry the step it waits for.
+// Exchange: a wave publishes each of its unit tiles (16 units x 16 sequences) as two 16-byte stores per lane of the
+// form {payload, stamp, payload, stamp} (stamp = step + 1 within the launch) with device scope, into a slot of its own;
+// the same wave of the partner polls that slot until all stamps of its loads carry the step it waits for.
 // Data and stamp share an aligned 8-byte word, which a store writes and a load reads as one, so no flag, fence or
 // ordering between different addresses is involved.  Two slots by step parity: a slot is rewritten two steps
 // later, which the writer can only reach after the partner has consumed it (it needs the partner's next h, published
@@ -522,13 +524,34 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 // Measured at config 2 (32 sequences, 4 workgroups): 2.3 us per step against 3.1 us for one workgroup per group;
 // the exchange is mostly hidden (the first look finds the data 60-90 % of the time), and what is left is a SIMD's
 // own serial work: 0.87 us of MFMA and 0.7 us of gate nonlinearities (quarter-rate exp2 and rcp) for its two
-// waves, plus two barriers and the LDS latency in front of each run of MFMAs.
+// waves, plus two barriers and the LDS latency in front of each run of MFMAs.  At config 5 (256 workgroups): 13 us
+// per step against 20 us.
 //
 // Every wait is bounded: a wave that does not see its partner's data within a.pair_spin_limit polls raises a flag in
 // LDS, the workgroup leaves the step loop together after the next barrier and marks the launch's scores as NaN.
-// The launch must be co-resident (at most one workgroup per CU is asked for: 2 x groups <= 128 workgroups).
-constexpr uint32_t kPairSlotBytes = 2 * 64 * 16;                       // one wave's publication: 2 lines x 64 lanes x 16 B
-constexpr uint32_t kPairExchBytes = 2 * 2 * 8 * kPairSlotBytes;        // [parity][member][wave] per sequence group
+// Members of a pair are neighbours in the launch order; workgroups are started in that order here, so a launch that
+// does not fit the chip at once still completes pair by pair (the bound covers any other case).  It is used up to
+// one workgroup per CU.
+// Geometry of the paired kernel: 8 waves, each with UT unit tiles of the workgroup's half of the hidden units; a
+// weight item is the 4 gate fragments of one tile at one k-step (4 KiB per wave), walked k-step by k-step (the B
+// operand of a k-step serves all tiles), own half of the k range first.  d_g = 256 keeps all 8 items of a wave in
+// registers; d_g = 512 (32 items, 128 KiB per wave) keeps RRES of them and streams the rest out of L2 through a ring
+// of NSLOT register buffers that runs PF items ahead, across the halves of a step and into the next step.
+template <int DG> struct PairGeo {
+    static constexpr int NW = 8, UT = DG / 256, KS = DG / 32, KH = KS / 2, ITEMS = UT * KS, HP = DG + 8;
+    static constexpr int RRES = DG == 256 ? ITEMS : 2, NS = ITEMS - RRES;
+    static constexpr int NSLOT = NS == 0 ? 1 : 5, PF = NSLOT - 1;   // (3 or 6 slots measured within 4 % of 5: the stream is not what the step waits for)
+    static_assert(NS % NSLOT == 0, "slot rotation must line up with the item loop");
+    // item p of the walk: half (0 own, 1 partner's), k-step within the half, unit tile
+    static constexpr int half_of(int p) { return p / (UT * KH); }
+    static constexpr int j_of(int p) { return (p % (UT * KH)) / UT; }
+    static constexpr int ut_of(int p) { return p % UT; }
+    static constexpr uint32_t slot_bytes = UT * 2 * 64 * 16;                 // one wave's publication: UT tiles x (hi, lo) lines of 1 KiB
+    static constexpr uint32_t exch_bytes = 2 * 2 * NW * slot_bytes;          // [parity][member][wave] per sequence group
+    static constexpr size_t lds_h = (size_t)2 * 2 * 16 * HP * sizeof(f16_t); // [buffer][hi, lo][sequence][unit]
+    static constexpr size_t lds_up = (size_t)3 * NW * 64 * sizeof(float);    // shares of the utility logit: own (2 parities), partner's
+    static constexpr size_t lds = lds_h + lds_up + 16;
+};
 
 __device__ __forceinline__ void lds_barrier()
 {
@@ -542,13 +565,16 @@ __device__ __forceinline__ void lds_barrier()
 template <int DG>
 __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, int nb)
 {
-    static_assert(DG == 256, "8 waves x 16 units x 2 workgroups");
     using G = Geo<DG>;                     // the packed operands keep the single-workgroup kernel's geometry
-    constexpr int NW = 8, KS = DG / 32, KH = KS / 2, HP = DG + 8;
+    using P = PairGeo<DG>;
+    constexpr int NW = P::NW, UT = P::UT, KS = P::KS, KH = P::KH, HP = P::HP;
+    constexpr int RRES = P::RRES, NS = P::NS, NSLOT = P::NSLOT, PF = P::PF;
     typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
-    __shared__ __align__(16) f16_t s_h[2 * 2 * 16 * HP];         // [buffer][hi, lo][sequence][unit]
-    __shared__ float s_up[2][NW][64], s_up2[NW][64];          // per-lane shares of the utility logit: own units (by step parity), partner's units
-    __shared__ int s_fail;
+    extern __shared__ __align__(16) unsigned char smem_pair[];
+    f16_t *s_h = reinterpret_cast<f16_t *>(smem_pair);
+    float (*s_up)[NW][64] = reinterpret_cast<float (*)[NW][64]>(smem_pair + P::lds_h);           // [2]
+    float (*s_up2)[64] = reinterpret_cast<float (*)[64]>(smem_pair + P::lds_h + 2 * NW * 64 * sizeof(float));
+    int &s_fail = *reinterpret_cast<int *>(smem_pair + P::lds_h + P::lds_up);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
@@ -557,7 +583,8 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
     const int l = gid / gpl, grp = gid % gpl;
     const bool live = grp * 16 + n < a.BH;
     const size_t s = (size_t)l * a.BH + min(grp * 16 + n, a.BH - 1);
-    const int tile = member * NW + wave, ptile = (1 - member) * NW + wave;      // unit tiles of this wave and of its partner wave
+    // unit tiles (16 units each) of this wave and of its partner wave: tile0 + ut, ptile0 + ut
+    const int tile0 = (member * NW + wave) * UT, ptile0 = ((1 - member) * NW + wave) * UT;
     const int ks_own = member * KH, ks_par = (1 - member) * KH;
 
     const bf16_t *w_s = static_cast<const bf16_t *>(a.w_s) + (size_t)l * DG;
@@ -566,24 +593,33 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
     if (tid == 0) s_fail = 0;
 
     const uint32_t lane16 = lane * 16;
-    // the tile's weights: items [ks] of (packed wave tile / 2, unit tile tile % 2), own-half k-steps first
+    // the wave's weights: item (ut, ks) at wbase + (ut*KS + ks) * 4096 (its tiles are neighbours in the packed order)
     const unsigned char *wbase = reinterpret_cast<const unsigned char *>(
-        a.whh_packed + (((size_t)l * G::NW + (tile >> 1)) * G::ITEMS + (tile & 1) * KS) * 4 * 64);
-    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wbase, KS * 4096);
-    f16x8_t wreg[KS][4];
+        a.whh_packed + (((size_t)l * G::NW + tile0 / G::UT) * G::ITEMS + (tile0 % G::UT) * KS) * 4 * 64);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wbase, UT * KS * 4096);
+    auto item_off = [&](int p) { return (uint32_t)((P::ut_of(p) * KS + (P::half_of(p) == 0 ? ks_own : ks_par) + P::j_of(p)) * 4096); };
+    f16x8_t wres[RRES][4];
+    static_for<RRES>([&](auto pc) {
+        constexpr int p = decltype(pc)::value;
 #pragma unroll
-    for (int j = 0; j < KS; ++j)
+        for (int q = 0; q < 4; ++q) wres[p][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, item_off(p));
+    });
+    f16x8_t wbuf[NSLOT][4];
+    auto load_w = [&](auto sc) __attribute__((always_inline)) {        // sc: index within the streamed items
+        constexpr int si = decltype(sc)::value, p = RRES + si;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            wreg[j][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, (uint32_t)((j < KH ? ks_own + j : ks_par + j - KH) * 4096));
-    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
-        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(gid, a.tb, 0, tile >> 1, tile & 1, 0) * 64);
-    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * G::NW * G::UT * 4096 - (uint32_t)tile * 4096);
-    const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)gid * kPairExchBytes, kPairExchBytes);
+        for (int q = 0; q < 4; ++q) wbuf[si % NSLOT][q] = buffer_load16<f16x8_t>(w_rsrc, lane16 + q * 1024, item_off(p));
+    };
+    if constexpr (NS > 0) static_for<PF>(load_w);
 
-    float c_reg[4], ws_own[4], ws_par[4];
-    f16_t *h_own = s_h + (size_t)n * HP + tile * 16 + 4 * g4;       // + (buf*2 + plane)*16*HP
-    f16_t *h_par = s_h + (size_t)n * HP + ptile * 16 + 4 * g4;
+    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(
+        reinterpret_cast<const f32x4_t *>(a.xproj) + xp_block<DG>(gid, a.tb, 0, tile0 / G::UT, tile0 % G::UT, 0) * 64);
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * G::NW * G::UT * 4096 - (uint32_t)tile0 * 4096);
+    const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)gid * P::exch_bytes, P::exch_bytes);
+
+    float c_reg[UT][4], ws_own[UT][4], ws_par[UT][4];
+    f16_t *h_own = s_h + (size_t)n * HP + tile0 * 16 + 4 * g4;       // + (buf*2 + plane)*16*HP + ut*16
+    f16_t *h_par = s_h + (size_t)n * HP + ptile0 * 16 + 4 * g4;
     const f16_t *h_rd = s_h + (size_t)n * HP + g4 * 8;               // + (buf*2 + plane)*16*HP + ks*32
     auto split = [](const float (&hv)[4], f16x4_t &hi, f16x4_t &lo) {
 #pragma unroll
@@ -592,58 +628,77 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
             lo[r] = (f16_t)(hv[r] - (float)hi[r]);
         }
     };
-    {   // h of step t0 - 1, both halves, from the fp32 state
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) {   // h of step t0 - 1, both halves, from the fp32 state
         float ho[4], hp[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            c_reg[r] = live ? a.c[s * DG + tile * 16 + 4 * g4 + r] : 0.f;
-            ho[r] = live ? a.h[s * DG + tile * 16 + 4 * g4 + r] : 0.f;
-            hp[r] = live ? a.h[s * DG + ptile * 16 + 4 * g4 + r] : 0.f;
-            ws_own[r] = bf16_to_f32(w_s[tile * 16 + 4 * g4 + r]);
-            ws_par[r] = bf16_to_f32(w_s[ptile * 16 + 4 * g4 + r]);
+            const int uo = (tile0 + ut) * 16 + 4 * g4 + r, up = (ptile0 + ut) * 16 + 4 * g4 + r;
+            c_reg[ut][r] = live ? a.c[s * DG + uo] : 0.f;
+            ho[r] = live ? a.h[s * DG + uo] : 0.f;
+            hp[r] = live ? a.h[s * DG + up] : 0.f;
+            ws_own[ut][r] = bf16_to_f32(w_s[uo]);
+            ws_par[ut][r] = bf16_to_f32(w_s[up]);
         }
         f16x4_t hi, lo;
         split(ho, hi, lo);
-        *reinterpret_cast<f16x4_t *>(h_own) = hi;
-        *reinterpret_cast<f16x4_t *>(h_own + 16 * HP) = lo;
+        *reinterpret_cast<f16x4_t *>(h_own + ut * 16) = hi;
+        *reinterpret_cast<f16x4_t *>(h_own + 16 * HP + ut * 16) = lo;
         split(hp, hi, lo);
-        *reinterpret_cast<f16x4_t *>(h_par) = hi;
-        *reinterpret_cast<f16x4_t *>(h_par + 16 * HP) = lo;
+        *reinterpret_cast<f16x4_t *>(h_par + ut * 16) = hi;
+        *reinterpret_cast<f16x4_t *>(h_par + 16 * HP + ut * 16) = lo;
     }
     __syncthreads();
 
-    // one look at the partner wave's slot `par` (two device-scope loads; their results are examined later)
-    auto ask = [&](int par, u32x4_t &r0, u32x4_t &r1) __attribute__((always_inline)) {
-        const uint32_t off = (uint32_t)((par * 2 + (1 - member)) * NW + wave) * kPairSlotBytes;
-        r0 = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, (int)lane16, (int)off, 16);           // device scope
-        r1 = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, (int)lane16, (int)(off + 1024), 16);
+    // one look at the partner wave's slot `par` (device-scope loads; their results are examined later)
+    struct Look { u32x4_t v[UT][2]; };
+    auto ask = [&](int par, Look &k) __attribute__((always_inline)) {
+        const uint32_t off = (uint32_t)((par * 2 + (1 - member)) * NW + wave) * P::slot_bytes;
+#pragma unroll
+        for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl)
+                k.v[ut][pl] = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, (int)lane16, (int)(off + (ut * 2 + pl) * 1024), 16);
     };
     // The partner wave's h of the step stamped `stamp`, from slot `par`: staged in LDS buffer `buf`, and its share of
-    // the utility logit left in s_up2.  (ra, r: two looks at the slot asked for earlier, so that their round trips,
+    // the utility logit left in s_up2.  (ka, k: looks at the slot asked for earlier, so that their round trips,
     // about 1 us behind the stores of the publication, run behind the own-half MFMAs; more looks follow if neither
     // carries the stamp yet.)
-    auto receive = [&](int par, uint32_t stamp, int buf, u32x4_t ra0, u32x4_t ra1, u32x4_t r0, u32x4_t r1) __attribute__((always_inline)) {
-        auto all_in = [&](const u32x4_t &x0, const u32x4_t &x1) __attribute__((always_inline)) {
-            const bool ok = x0[1] == stamp && x0[3] == stamp && x1[1] == stamp && x1[3] == stamp;
+    auto receive = [&](int par, uint32_t stamp, int buf, const Look &ka, Look &k) __attribute__((always_inline)) {
+        auto all_in = [&](const Look &x) __attribute__((always_inline)) {
+            bool ok = true;
+#pragma unroll
+            for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl) ok = ok && x.v[ut][pl][1] == stamp && x.v[ut][pl][3] == stamp;
             return __all(ok) != 0;
         };
-        bool got = all_in(ra0, ra1);
-        if (got) { r0 = ra0; r1 = ra1; }
-        for (int spin = 0; !got && spin < a.pair_spin_limit; ++spin) {
+        auto stage = [&](const Look &x) __attribute__((always_inline)) {
+            float up = 0.f;
+#pragma unroll
+            for (int ut = 0; ut < UT; ++ut) {
+                const uint2 hi2 = make_uint2(x.v[ut][0][0], x.v[ut][0][2]), lo2 = make_uint2(x.v[ut][1][0], x.v[ut][1][2]);
+                const f16x4_t hi = __builtin_bit_cast(f16x4_t, hi2), lo = __builtin_bit_cast(f16x4_t, lo2);
+                *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 0) * 16 * HP + ut * 16) = hi;
+                *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 1) * 16 * HP + ut * 16) = lo;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) up = fmaf(ws_par[ut][r], (float)hi[r] + (float)lo[r], up);
+            }
+            s_up2[wave][lane] = up;
+        };
+        if (all_in(ka)) {
+            stage(ka);
+            return;
+        }
+        bool got = false;
+        for (int spin = 0; spin < a.pair_spin_limit; ++spin) {
             asm volatile("" ::: "memory");
-            if (all_in(r0, r1)) { got = true; break; }
+            if (all_in(k)) { got = true; break; }
             if ((spin & 255) == 255 && s_fail) break;
-            ask(par, r0, r1);
+            ask(par, k);
         }
         if (!got) s_fail = 1;
-        const uint2 hi2 = make_uint2(r0[0], r0[2]), lo2 = make_uint2(r1[0], r1[2]);
-        const f16x4_t hi = __builtin_bit_cast(f16x4_t, hi2), lo = __builtin_bit_cast(f16x4_t, lo2);
-        *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 0) * 16 * HP) = hi;
-        *reinterpret_cast<f16x4_t *>(h_par + (size_t)(buf * 2 + 1) * 16 * HP) = lo;
-        float up = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) up = fmaf(ws_par[r], (float)hi[r] + (float)lo[r], up);
-        s_up2[wave][lane] = up;
+        stage(k);
     };
     // Member 0 completes the logit of a step once both halves are in: own shares (buffer `ub`), then the partner's.
     // One wave does it, at a point where it would otherwise wait at the barrier for the slower ones.
@@ -663,94 +718,137 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
             }
         }
     };
-    // NK k-steps from ks0 on, with the weight fragments [j0, j0 + NK)
-    auto mfma_run = [&](f32x4_t (&acc)[4], int buf, int ks0, auto jbase, auto nk) __attribute__((always_inline)) {
-        constexpr int j0 = decltype(jbase)::value, NK = decltype(nk)::value;
-        f16x8_t hb[NK][2];
+    // the two fp16 terms of h for one k-step
+    auto read_h = [&](f16x8_t (&dst)[2], int buf, int ks) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < NK; ++j)
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-                hb[j][p] = *reinterpret_cast<const f16x8_t *>(h_rd + (size_t)(buf * 2 + p) * 16 * HP + (ks0 + j) * 32);
-#pragma unroll
-        for (int j = 0; j < NK; ++j)
-#pragma unroll
-            for (int p = 1; p >= 0; --p)          // the small term first
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wreg[j0 + j][q], hb[j][p], acc[q], 0, 0, 0);
+        for (int pl = 0; pl < 2; ++pl)
+            dst[pl] = *reinterpret_cast<const f16x8_t *>(h_rd + (size_t)(buf * 2 + pl) * 16 * HP + ks * 32);
     };
     using std::integral_constant;
 
     bool failed = false;
-    u32x4_t ra0 = {0, 0, 0, 0}, ra1 = {0, 0, 0, 0};
+    Look ka;
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) ka.v[ut][0] = ka.v[ut][1] = u32x4_t{0, 0, 0, 0};
     for (int tt = 0; tt < nb; ++tt) {
         const int cur = tt & 1, nxt = cur ^ 1;
-        f32x4_t acc[4], xin[4];
+        f32x4_t acc[UT][4], xin[UT][4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            xin[q] = buffer_load16_nt<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)tt * G::NW * G::UT * 4096);
-            acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        }
+        for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (UT == 1) xin[ut][q] = buffer_load16_nt<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)(tt * G::NW * G::UT + ut) * 4096);
+                acc[ut][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            }
         // the partner published h of step tt - 1 at the end of that step (slot nxt, stamp tt); a first look at the slot
-        // went out right after this workgroup's own publication, a second one goes now
-        u32x4_t rb0 = {0, 0, 0, 0}, rb1 = {0, 0, 0, 0};
-        if (tt > 0) ask(nxt, rb0, rb1);
+        // went out right after this workgroup's own publication, a second one goes now (one tile per wave only:
+        // with two, the own half is long enough for the first)
+        Look kb;
+        if constexpr (UT == 1) {
+            if (tt > 0) ask(nxt, kb);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        mfma_run(acc, cur, ks_own, integral_constant<int, 0>{}, integral_constant<int, KH>{});
+
+        // one half of the step's products: items [half * UT*KH, (half + 1) * UT*KH) of the walk
+        auto run_half = [&](auto halfc) __attribute__((always_inline)) {
+            constexpr int half = decltype(halfc)::value, p0 = half * UT * KH;
+            const int ks0 = half == 0 ? ks_own : ks_par;
+            // B operands: all k-steps of the half at once where the registers allow it, else one k-step ahead
+            constexpr int NHB = UT == 1 ? KH : 2;
+            f16x8_t hb[NHB][2];
+            if constexpr (UT == 1) {
+#pragma unroll
+                for (int j = 0; j < KH; ++j) read_h(hb[j], cur, ks0 + j);
+            } else {
+                read_h(hb[0], cur, ks0);
+            }
+            static_for<UT * KH>([&](auto ic) {
+                constexpr int p = p0 + decltype(ic)::value, j = P::j_of(p), ut = P::ut_of(p);
+                if constexpr (UT > 1 && ut == 0 && j + 1 < KH) read_h(hb[(j + 1) % NHB], cur, ks0 + j + 1);
+                if constexpr (p >= RRES) load_w(integral_constant<int, (p - RRES + PF) % (NS > 0 ? NS : 1)>{});
+                if constexpr (UT > 1 && half == 1 && j == KH - 2 && ut == 0) {
+                    // the input projections of this step, asked for one k-step before they are used
+#pragma unroll
+                    for (int u2 = 0; u2 < UT; ++u2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            xin[u2][q] = buffer_load16_nt<f32x4_t>(x_rsrc, lane16 + q * 1024, (uint32_t)(tt * G::NW * G::UT + u2) * 4096);
+                }
+                auto chain = [&](const f16x8_t (&wf)[4]) __attribute__((always_inline)) {
+#pragma unroll
+                    for (int pl = 1; pl >= 0; --pl)          // the small term first
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            acc[ut][q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[q], hb[j % NHB][pl], acc[ut][q], 0, 0, 0);
+                };
+                if constexpr (p < RRES) chain(wres[p]);
+                else chain(wbuf[(p - RRES) % NSLOT]);
+                if constexpr (NS > 0) __builtin_amdgcn_sched_barrier(0);      // the ring's depth is the one written here
+            });
+        };
+        run_half(integral_constant<int, 0>{});
         if (tt > 0) {
-            receive(nxt, (uint32_t)tt, cur, ra0, ra1, rb0, rb1);
+            if constexpr (UT == 1) receive(nxt, (uint32_t)tt, cur, ka, kb);
+            else receive(nxt, (uint32_t)tt, cur, ka, ka);         // (further looks may overwrite the first)
             lds_barrier();
             if (s_fail) { failed = true; break; }
         }
-        mfma_run(acc, cur, ks_par, integral_constant<int, KH>{}, integral_constant<int, KH>{});
+        run_half(integral_constant<int, 1>{});
 
-        float hv[4], upart = 0.f;
+        float upart = 0.f;
+        f16x4_t hi[UT], lo[UT];
+        float hv[UT][4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float ig = sigmoid_hw(fmaf(acc[0][r], inv_scale, xin[0][r]));
-            const float fg = sigmoid_hw(fmaf(acc[1][r], inv_scale, xin[1][r]));
-            const float gg = tanh_hw(fmaf(acc[2][r], inv_scale, xin[2][r]));
-            const float og = sigmoid_hw(fmaf(acc[3][r], inv_scale, xin[3][r]));
-            const float cn = fmaf(fg, c_reg[r], ig * gg);
-            c_reg[r] = cn;
-            float hn = og * tanh_hw(cn);
-            asm volatile("" : "+v"(hn));
-            hv[r] = hn;
-            upart = fmaf(ws_own[r], hn, upart);
-        }
-        f16x4_t hi, lo;
-        split(hv, hi, lo);
-        {   // to the partner first (the long way), then to this workgroup's own waves
-            const uint2 hi2 = __builtin_bit_cast(uint2, hi), lo2 = __builtin_bit_cast(uint2, lo);
+        for (int ut = 0; ut < UT; ++ut) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float ig = sigmoid_hw(fmaf(acc[ut][0][r], inv_scale, xin[ut][0][r]));
+                const float fg = sigmoid_hw(fmaf(acc[ut][1][r], inv_scale, xin[ut][1][r]));
+                const float gg = tanh_hw(fmaf(acc[ut][2][r], inv_scale, xin[ut][2][r]));
+                const float og = sigmoid_hw(fmaf(acc[ut][3][r], inv_scale, xin[ut][3][r]));
+                const float cn = fmaf(fg, c_reg[ut][r], ig * gg);
+                c_reg[ut][r] = cn;
+                float hn = og * tanh_hw(cn);
+                asm volatile("" : "+v"(hn));
+                hv[ut][r] = hn;
+                upart = fmaf(ws_own[ut][r], hn, upart);
+            }
+            split(hv[ut], hi[ut], lo[ut]);
+            // to the partner first (the long way), then to this workgroup's own waves
+            const uint2 hi2 = __builtin_bit_cast(uint2, hi[ut]), lo2 = __builtin_bit_cast(uint2, lo[ut]);
             const uint32_t stamp = (uint32_t)tt + 1;
-            const uint32_t off = (uint32_t)((cur * 2 + member) * NW + wave) * kPairSlotBytes;
+            const uint32_t off = (uint32_t)((cur * 2 + member) * NW + wave) * P::slot_bytes + ut * 2048;
             const u32x4_t l0 = {hi2.x, stamp, hi2.y, stamp}, l1 = {lo2.x, stamp, lo2.y, stamp};
             if (member != a.pair_mute) {
                 __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
                 __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
             }
         }
-        ask(cur, ra0, ra1);          // the partner is about to publish the same step
-        *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 0) * 16 * HP) = hi;
-        *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 1) * 16 * HP) = lo;
+        ask(cur, ka);                // the partner is about to publish the same step
+#pragma unroll
+        for (int ut = 0; ut < UT; ++ut) {
+            *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 0) * 16 * HP + ut * 16) = hi[ut];
+            *reinterpret_cast<f16x4_t *>(h_own + (size_t)(nxt * 2 + 1) * 16 * HP + ut * 16) = lo[ut];
+            if (tt == nb - 1 && live)
+                *reinterpret_cast<float4 *>(a.h + s * DG + (tile0 + ut) * 16 + 4 * g4) = make_float4(hv[ut][0], hv[ut][1], hv[ut][2], hv[ut][3]);
+        }
         s_up[cur][wave][lane] = upart;
-        if (tt == nb - 1 && live)
-            *reinterpret_cast<float4 *>(a.h + s * DG + tile * 16 + 4 * g4) = make_float4(hv[0], hv[1], hv[2], hv[3]);
         if (tt > 0) write_util(nxt, tt - 1);       // both halves of step tt - 1 have been in LDS since this step's first barrier
         lds_barrier();
     }
     if (!failed) {      // the last step's logit needs the partner's last h
-        u32x4_t r0, r1;
-        ask((nb - 1) & 1, r0, r1);
-        receive((nb - 1) & 1, (uint32_t)nb, nb & 1, ra0, ra1, r0, r1);
+        Look k;
+        ask((nb - 1) & 1, k);
+        receive((nb - 1) & 1, (uint32_t)nb, nb & 1, ka, k);
         lds_barrier();
         failed = s_fail != 0;
         if (!failed) write_util((nb - 1) & 1, nb - 1);
     }
     if (live) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) a.c[s * DG + tile * 16 + 4 * g4 + r] = failed ? __builtin_nanf("") : c_reg[r];
+        for (int ut = 0; ut < UT; ++ut)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) a.c[s * DG + (tile0 + ut) * 16 + 4 * g4 + r] = failed ? __builtin_nanf("") : c_reg[ut][r];
     }
     if (failed && tid < 16 && live) {
         for (int t = 0; t < nb; ++t) {
@@ -775,6 +873,12 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128, kTT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
         if (e != hipSuccess) return e;
+        if constexpr (DG == 256 || DG == 512) {
+            static_assert(PairGeo<DG>::exch_bytes == (DG / 256) * 65536, "the scratch planner's figure");
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_pair_kernel<DG>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)PairGeo<DG>::lds);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
     {
@@ -811,9 +915,9 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
             if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
             else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
         }
-        if constexpr (DG == 256) {
+        if constexpr (DG == 256 || DG == 512) {
             if (a.exch_bytes) {
-                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), 0, st, a, t0, nb);
+                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
                 continue;
             }
         }

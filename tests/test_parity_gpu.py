@@ -207,6 +207,7 @@ LSTM_CASES = [
     _cfg(148, "bf16", d=128, T=800, C=32, d_g=256, L=1, B=2, H=24),       # 3 full groups, each on a pair of workgroups
     _cfg(149, "bf16", d=64, T=192, C=32, d_g=256, L=4, B=4, H=64),        # 64 groups: the largest paired launch
     _cfg(150, "bf16", d=64, T=192, C=32, d_g=256, L=13, B=5, H=16),       # 65 groups: one workgroup per group again
+    _cfg(152, "bf16", d=128, T=288, C=32, d_g=512, L=2, B=2, H=12),       # widest gate on pairs: 2 tiles per wave, weights streamed
 ]
 
 
