@@ -110,8 +110,8 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  * kvev_workspace_bytes (fp32 input projections of a block of steps); any size
  * from one step's worth up is accepted, smaller blocks mean more launches.
  * Calls that share a workspace must not overlap (it also carries what the
- * workgroups of one launch exchange).  Small launches (bf16, d_g = 256, at
- * most 64 groups of 16 sequences) run each group on two cooperating
+ * workgroups of one launch exchange).  Small launches (bf16; d_g = 256 with at
+ * most 64 groups of 16 sequences, d_g = 512 with at most 128) run each group on two cooperating
  * workgroups, which wait for each other's data with a bounded number of polls;
  * should the bound ever expire (the GPU held by other work for seconds), the
  * launch ends normally and its util, gate and c entries are NaN.
