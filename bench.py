@@ -84,6 +84,25 @@ def rec_kernel_name(cfg):
     return f"lstm_rec_pair_kernel<{cfg.d_g}>" if paired else f"lstm_rec_kernel<{cfg.d_g}>"
 
 
+def recurrence_occupancy(cfg, gate_us):
+    """The recurrence is N dependent steps on the few compute units its sequences occupy, so its share of the whole
+    chip's MFMA peak says little.  This is the local figure: clocks the matrix pipe of an occupied SIMD needs for one
+    step (two fp16 terms per weight fragment, 16 clocks per 16x16x32 instruction, 2.4 GHz) over the measured time per
+    step (the whole gate call, so a lower bound on the recurrence kernel's own utilisation; profiles/mfma_counters.md
+    has the counter-based figure)."""
+    groups = cfg.L * ((cfg.B * cfg.H + 15) // 16)
+    paired = rec_kernel_name(cfg).startswith("lstm_rec_pair")
+    cus = min(256, groups * (2 if paired else 1))
+    rounds = -(-groups * (2 if paired else 1) // 256)
+    mfma_per_group_step = 2 * (4 * cfg.d_g // 16) * (cfg.d_g // 32)
+    per_simd = mfma_per_group_step / (2 if paired else 1) / 4 * rounds
+    us_step = gate_us / cfg.N
+    busy_us = per_simd * 16 / 2400.0
+    return {"dependent_steps": cfg.N, "us_per_step": round(us_step, 3), "compute_units_occupied": cus,
+            "workgroups_per_sequence_group": 2 if paired else 1,
+            "mfma_pipe_us_per_step_per_simd": round(busy_us, 3), "mfma_pipe_busy_frac_of_occupied_simds": round(busy_us / us_step, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -214,6 +233,8 @@ def main():
     rooflines = [roof(n, kernels[n], cost[n], stage_us[n], bounds[n]) for n, _ in stages if stage_us[n] > 0]
     for r in rooflines:
         r["traffic"] = measured_traffic(cfg.name, r["stage"])
+        if r["stage"] == "gate" and mfma and cfg.d_g in (64, 128, 256, 512):
+            r["recurrence"] = recurrence_occupancy(cfg, r["us_per_launch"])
     out = {
         "metric": "gated-chunk decode attn tokens/s per layer", "value": round(value, 2), "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
