@@ -252,7 +252,7 @@ def main():
     if rooflines:
         dom = max(rooflines, key=lambda r: r["us_per_launch"])
         out["roofline"] = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "stage", "kernel",
-                                              "us_per_launch")}
+                                              "us_per_launch", "recurrence") if k in dom}
         out["rooflines"] = rooflines
 
     if not args.only:
