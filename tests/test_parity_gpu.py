@@ -234,12 +234,12 @@ def test_lstm_gate(cfg):
     gate = torch.full_like(util, 9.0)
     ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
     Kb, Vb = Kbar.cuda(), Vbar.cuda()
-    # cut into three calls that carry the state, the middle one with a small workspace
+    # cut into three calls that carry the state: the first with scratch for one step per launch, the second for two
     cuts = [(0, min(3, N)), (min(3, N), min(N, 20)), (min(N, 20), N)]
     for i, (a, b) in enumerate(cuts):
         w_i = ws
-        if i == 1:
-            w_i = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, 2))
+        if i < 2:
+            w_i = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, i + 1))
         kb.kvev_lstm_gate(sh, Kb, Vb, kb.lstm_weights(gw), a, b, h, c, util, gate, w_i)
     torch.cuda.synchronize()
     rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
