@@ -162,7 +162,7 @@ def main():
     def pool(t): kb.kvev_chunk_pool(sh, t["K"], t["V"], kb.POOL_MLP, wK, wV, 0, N, st.Kbar, st.Vbar, st.ws)
 
     def gate(t):
-        st.h.zero_(); st.c.zero_()
+        st.hc.zero_()                # the cold step starts the recurrence from a zero state (one fill for h and c)
         kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, lw, 0, N, st.h, st.c, st.util, st.gate, st.ws)
 
     def select(t): kb.kvev_select(sh, st.util, st.gate, kb.SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)
@@ -478,7 +478,7 @@ def main():
                                             s4.k_cap, O4, s4.ws)
                 return n4
             for rep in range(2):                      # first pass warms up, second is timed
-                s4.h.zero_(); s4.c.zero_()
+                s4.hc.zero_()
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -529,7 +529,7 @@ def main():
                 return n4, ncand
             O_ref = O4.clone()                           # last decode of the indexed stream (same queries)
             for rep in range(2):
-                s4.h.zero_(); s4.c.zero_(); cn4.zero_()
+                s4.hc.zero_(); cn4.zero_()
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()

@@ -207,8 +207,8 @@ class DecodeState:
         lead = (cfg.L, cfg.B, cfg.kv_heads)       # summaries, gate state and kept sets exist per key-value head
         self.Kbar = torch.zeros(lead + (self.N_cap, cfg.d), dtype=dt, device=dev)
         self.Vbar = torch.zeros_like(self.Kbar)
-        self.h = torch.zeros(lead + (cfg.d_g,), dtype=torch.float32, device=dev)
-        self.c = torch.zeros_like(self.h)
+        self.hc = torch.zeros((2,) + lead + (cfg.d_g,), dtype=torch.float32, device=dev)    # one buffer: one fill resets both
+        self.h, self.c = self.hc[0], self.hc[1]
         self.util = torch.zeros(lead + (self.N_cap,), dtype=torch.float32, device=dev)
         self.gate = torch.zeros_like(self.util)
         self.idx = torch.full(lead + (max(self.k_cap, 1),), -1, dtype=torch.int32, device=dev)
@@ -241,8 +241,7 @@ def cold_step(st: DecodeState, t: Dict[str, torch.Tensor], O: torch.Tensor, T: O
     if T is not None:
         sh.T = T
     N = sh.T // cfg.C
-    st.h.zero_()
-    st.c.zero_()
+    st.hc.zero_()
     kvev_chunk_pool(sh, t["K"], t["V"], pool_mode, mlp_weights(t, "K"), mlp_weights(t, "V"), 0, N,
                     st.Kbar, st.Vbar, st.ws)
     kvev_lstm_gate(sh, st.Kbar, st.Vbar, lstm_weights(t), 0, N, st.h, st.c, st.util, st.gate, st.ws)
