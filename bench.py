@@ -162,7 +162,6 @@ def main():
     def pool(t): kb.kvev_chunk_pool(sh, t["K"], t["V"], kb.POOL_MLP, wK, wV, 0, N, st.Kbar, st.Vbar, st.ws)
 
     def gate(t):
-        st.hc.zero_()                # the cold step starts the recurrence from a zero state (one fill for h and c)
         kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, lw, 0, N, st.h, st.c, st.util, st.gate, st.ws)
 
     def select(t): kb.kvev_select(sh, st.util, st.gate, kb.SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)

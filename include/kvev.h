@@ -102,9 +102,11 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  *   (i,f,g,o) = W_ih x_t + b_ih + W_hh h_{t-1} + b_hh;  c_t = s(f) c_{t-1} + s(i) tanh(g);
  *   h_t = s(o) tanh(c_t);   util_t = w_s . h_t + b_s;   gate_t = s(util_t) in [0,1].
  * State, pre-activations and scores are fp32.
- *   h, c        [L,B,H,d_g] fp32, in/out: the caller zeroes them before the
- *               first call of a stream (chunk_begin == 0) and passes them back
- *               unchanged to continue it
+ *   h, c        [L,B,H,d_g] fp32, in/out: a call with chunk_begin == 0 starts
+ *               from the zero state h_0 = c_0 = 0 whatever they hold (nothing
+ *               to clear), and leaves the state after chunk_end - 1 in them;
+ *               pass them back unchanged to continue the stream
+ *               (chunk_begin > 0)
  *   util, gate  [L,B,H,N_cap] fp32, entries [chunk_begin, chunk_end) written
  * Needs 0 <= chunk_begin <= chunk_end <= N_cap.  Workspace: see
  * kvev_workspace_bytes (fp32 input projections of a block of steps); any size

@@ -241,7 +241,6 @@ def cold_step(st: DecodeState, t: Dict[str, torch.Tensor], O: torch.Tensor, T: O
     if T is not None:
         sh.T = T
     N = sh.T // cfg.C
-    st.hc.zero_()
     kvev_chunk_pool(sh, t["K"], t["V"], pool_mode, mlp_weights(t, "K"), mlp_weights(t, "V"), 0, N,
                     st.Kbar, st.Vbar, st.ws)
     kvev_lstm_gate(sh, st.Kbar, st.Vbar, lstm_weights(t), 0, N, st.h, st.c, st.util, st.gate, st.ws)

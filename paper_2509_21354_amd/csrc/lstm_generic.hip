@@ -27,9 +27,10 @@ __global__ __launch_bounds__(256) void lstm_generic_kernel(LstmArgs a)
     const T *w_s = static_cast<const T *>(a.w_s) + (size_t)l * dg;
     const float b_s = Storage<T>::load(static_cast<const T *>(a.b_s) + l);
 
+    const bool fresh = a.c0 == 0;        // the recurrence starts from a zero state at chunk 0, whatever the buffers hold
     for (int j = tid; j < dg; j += 256) {
-        h[j] = a.h[(size_t)s * dg + j];
-        c[j] = a.c[(size_t)s * dg + j];
+        h[j] = fresh ? 0.f : a.h[(size_t)s * dg + j];
+        c[j] = fresh ? 0.f : a.c[(size_t)s * dg + j];
     }
     for (int t = a.c0; t < a.c1; ++t) {
         const size_t row = ((size_t)s * a.N_cap + t) * D;

@@ -342,8 +342,9 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int unit = wave * 16 * UT + ut * 16 + 4 * g4 + r;
-            c_reg[ut][r] = live ? a.c[s * DG + unit] : 0.f;
-            h_reg[ut][r] = live ? a.h[s * DG + unit] : 0.f;
+            // (chunk 0 starts the recurrence from a zero state, whatever the buffers hold)
+            c_reg[ut][r] = live && t0 > 0 ? a.c[s * DG + unit] : 0.f;
+            h_reg[ut][r] = live && t0 > 0 ? a.h[s * DG + unit] : 0.f;
             ws_reg[ut][r] = bf16_to_f32(w_s[unit]);
         }
 
@@ -634,9 +635,10 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int uo = (tile0 + ut) * 16 + 4 * g4 + r, up = (ptile0 + ut) * 16 + 4 * g4 + r;
-            c_reg[ut][r] = live ? a.c[s * DG + uo] : 0.f;
-            ho[r] = live ? a.h[s * DG + uo] : 0.f;
-            hp[r] = live ? a.h[s * DG + up] : 0.f;
+            // (chunk 0 starts the recurrence from a zero state, whatever the buffers hold)
+            c_reg[ut][r] = live && t0 > 0 ? a.c[s * DG + uo] : 0.f;
+            ho[r] = live && t0 > 0 ? a.h[s * DG + uo] : 0.f;
+            hp[r] = live && t0 > 0 ? a.h[s * DG + up] : 0.f;
             ws_own[ut][r] = bf16_to_f32(w_s[uo]);
             ws_par[ut][r] = bf16_to_f32(w_s[up]);
         }

@@ -228,8 +228,9 @@ def test_lstm_gate(cfg):
     sh = kb.make_shape(cfg, N_cap=N_cap)
     lead = (cfg.L, cfg.B, cfg.H)
     gw = dev(w)
-    h = torch.zeros(lead + (cfg.d_g,), device="cuda")
-    c = torch.zeros_like(h)
+    # a call that begins at chunk 0 starts from the zero state whatever h and c hold
+    h = torch.full(lead + (cfg.d_g,), 7.0, device="cuda")
+    c = torch.full_like(h, float("nan"))
     util = torch.full(lead + (N_cap,), 9.0, device="cuda")
     gate = torch.full_like(util, 9.0)
     ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
