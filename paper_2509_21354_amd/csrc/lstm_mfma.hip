@@ -6,7 +6,10 @@
 //                       exact in the fp32 accumulator), written to scratch in
 //                       the exact register layout the recurrence reads back;
 //   lstm_rec_kernel     the sequential half: one workgroup owns 16 sequences
-//                       of one layer and walks them through the block's steps.
+//                       of one layer and walks them through the block's steps;
+//   lstm_rec_pair_kernel  the same on two workgroups per 16 sequences, each
+//                       with half of the hidden units, for launches small enough
+//                       to be resident at once (further down).
 //
 // Tiling (both kernels): v_mfma_f32_16x16x32_bf16 with the gate rows as the M
 // side (A operand = weight rows, read straight from global memory / L2 in
