@@ -582,8 +582,14 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
-    const int member = blockIdx.x & 1, gid = blockIdx.x >> 1;
+    // Workgroup ids go round-robin over the 8 XCDs: ids b and b + 8 land on the same one.  With the weights in registers
+    // (d_g = 256) the members of a pair are 8 apart, so that both sit behind one L2 (2 % faster at config 2; ids past
+    // the last pair have nothing to do).  With streamed weights (d_g = 512) they are neighbours instead, so that an
+    // XCD's L2 serves one half of W_hh only: at config 5, 8.8 against 9.7 ms.
+    const int xcd = blockIdx.x & 7, row = blockIdx.x >> 3;
+    const int member = UT == 1 ? row & 1 : blockIdx.x & 1, gid = UT == 1 ? (row >> 1) * 8 + xcd : blockIdx.x >> 1;
     const int gpl = (a.BH + 15) / 16;
+    if (gid >= a.L * gpl) return;
     const int l = gid / gpl, grp = gid % gpl;
     const bool live = grp * 16 + n < a.BH;
     const size_t s = (size_t)l * a.BH + min(grp * 16 + n, a.BH - 1);
@@ -922,7 +928,8 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         }
         if constexpr (DG == 256 || DG == 512) {
             if (a.exch_bytes) {
-                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
+                const unsigned pair_grid = DG == 256 ? 16 * ((groups + 7) / 8) : 2 * groups;      // (the kernel's two id orders)
+                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(pair_grid), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
                 continue;
             }
         }
