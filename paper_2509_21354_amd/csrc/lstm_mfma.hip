@@ -525,7 +525,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 //   own-half MFMAs | take partner's h, stage in LDS | barrier | partner-half MFMAs | cell, publish | barrier.
 // The utility logit w_s . h_t + b_s is completed one step later, when the partner's half has arrived (as hi + lo,
 // 22 bits); one wave of member 0 writes it while it would otherwise wait at the step's last barrier.
-// Measured at config 2 (32 sequences, 4 workgroups): 2.3 us per step against 3.1 us for one workgroup per group;
+// Measured at config 2 (32 sequences, 4 workgroups): 2.1 us per step against 3.1 us for one workgroup per group;
 // the exchange is mostly hidden (the first look finds the data 60-90 % of the time), and what is left is a SIMD's
 // own serial work: 0.87 us of MFMA and 0.7 us of gate nonlinearities (quarter-rate exp2 and rcp) for its two
 // waves, plus two barriers and the LDS latency in front of each run of MFMAs.  At config 5 (256 workgroups): 13 us
