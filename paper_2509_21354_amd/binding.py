@@ -72,7 +72,7 @@ def lib() -> ctypes.CDLL:
         L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_workspace_bytes.argtypes = [ci, shp, ci, ci]
         L.kvev_workspace_bytes.restype = sz
-        L.kvev_debug_pair_wait.argtypes = [ci, ci]
+        L.kvev_debug_pair_wait.argtypes = [ci, ci, ci]
         L.kvev_debug_pair_wait.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
@@ -126,8 +126,8 @@ def make_shape(cfg=None, **kw) -> Shape:
     return Shape(**v)
 
 
-def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> None:
-    _check(lib().kvev_debug_pair_wait(spin_limit, mute_member), "kvev_debug_pair_wait")
+def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1, write_through: int = 0) -> None:
+    _check(lib().kvev_debug_pair_wait(spin_limit, mute_member, write_through), "kvev_debug_pair_wait")
 
 
 def workspace_bytes(op: int, shape: Shape, n: int, k_cap: int = 0) -> int:

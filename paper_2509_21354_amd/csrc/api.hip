@@ -137,7 +137,7 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
 
 // Bound on the polls of one wait of the paired recurrence (each poll is a round trip to memory, about a
 // microsecond: seconds in all), and the member whose publications are withheld; kvev_debug_pair_wait changes them.
-static int g_pair_spin_limit = 1 << 22, g_pair_mute = -1;
+static int g_pair_spin_limit = 1 << 22, g_pair_mute = -1, g_pair_write_through = 0;
 
 static long long lstm_groups(const kvev_shape *sh)
 {
@@ -250,6 +250,7 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         a.exch_bytes = lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh));
         a.pair_spin_limit = g_pair_spin_limit;
         a.pair_mute = g_pair_mute;
+        a.pair_write_through = g_pair_write_through;
         a.exch = a.exch_bytes ? static_cast<unsigned char *>(ws) + lstm_ws_weights(sh) : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
@@ -325,11 +326,13 @@ int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, co
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 
-int kvev_debug_pair_wait(int spin_limit, int mute_member)
+int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through)
 {
-    if (spin_limit < 1 || mute_member < -1 || mute_member > 1) return KVEV_ERR_INVALID_ARG;
+    if (spin_limit < 1 || mute_member < -1 || mute_member > 1 || write_through < 0 || write_through > 1)
+        return KVEV_ERR_INVALID_ARG;
     g_pair_spin_limit = spin_limit;
     g_pair_mute = mute_member;
+    g_pair_write_through = write_through;
     return KVEV_OK;
 }
 

@@ -44,6 +44,7 @@ struct LstmArgs {
     size_t exch_bytes;    // 0: one workgroup per sequence group
     int pair_spin_limit;  // polls a wave of the paired recurrence spends on one wait before it gives up
     int pair_mute;        // member (0, 1) whose publications are withheld, -1: none (failure-path tests only)
+    int pair_write_through;   // 1: publish with device-scope stores even behind a shared L2 (tests of that path)
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block

@@ -684,7 +684,7 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
         if (lane == 0) s_near = near;          // (no answer within the bound: write through; the step waits will expire too)
     }
     __syncthreads();
-    const bool near = s_near != 0;
+    const bool near = s_near != 0 && !a.pair_write_through;
 
     // one look at the partner wave's slot `par` (device-scope loads; their results are examined later)
     struct Look { u32x4_t v[UT][2]; };

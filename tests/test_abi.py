@@ -31,10 +31,11 @@ def test_library_exports_every_declared_symbol():
 
 def test_debug_pair_wait_validation():
     L = kb.lib()
-    assert L.kvev_debug_pair_wait(0, -1) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(16, 2) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(16, -2) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(1 << 22, -1) == kb.OK      # the defaults
+    assert L.kvev_debug_pair_wait(0, -1, 0) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, 2, 0) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, -2, 0) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, -1, 2) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(1 << 22, -1, 0) == kb.OK      # the defaults
 
 
 FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first

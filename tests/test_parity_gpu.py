@@ -285,6 +285,13 @@ def test_lstm_pair_wait_expires_cleanly():
     rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
     assert np.abs(util.cpu().numpy() - ru).max() <= SCORE_TOL
     assert np.abs(c.cpu().numpy() - rc).max() <= 2 * SCORE_TOL
+    # the publication through write-through stores (what pairs that do not share an L2 use) gives the same bits
+    kb.kvev_debug_pair_wait(write_through=1)
+    try:
+        h2, c2, util2, gate2 = run()
+    finally:
+        kb.kvev_debug_pair_wait()
+    assert torch.equal(util, util2) and torch.equal(gate, gate2) and torch.equal(h, h2) and torch.equal(c, c2)
 
 
 def _run_cold(cfg, t, g):
