@@ -149,7 +149,12 @@ int kvev_select(const kvev_shape *shape, const float *util, const float *gate, i
  * rows at all gives O = 0.
  *   Q, O  [L,B,H,Tq,d]    idx [L,B,H,k_cap]   count [L,B,H], 0 <= count <= k_cap,
  *   every idx entry below count in [0, N_cand) (not checked: device data).
- * Workspace: split partials, see kvev_workspace_bytes. */
+ * Workspace: see kvev_workspace_bytes (0 when the launch needs no split).  It
+ * begins with one int32 ticket per (sequence, query group), followed by the
+ * split partials.  The tickets must be zero when a call starts and every call
+ * leaves them zero: fill a fresh workspace with zeros once, and again only
+ * after lending it to something else (kvev_lstm_gate writes all over its own).
+ * Calls that share a workspace must not overlap. */
 int kvev_gated_attention(const kvev_shape *shape, const void *Q, int Tq, const void *K,
                          const void *V, const void *Kbar, const void *Vbar, const int32_t *idx,
                          const int32_t *count, int k_cap, int causal, void *O, void *ws,

@@ -135,7 +135,8 @@ def workspace_bytes(op: int, shape: Shape, n: int, k_cap: int = 0) -> int:
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
-    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    """Scratch for one op, zero-filled: the attention calls keep their split tickets in it, which start at zero."""
+    return torch.zeros(max(nbytes, 16), dtype=torch.uint8, device=device)
 
 
 def _mlp(w: Optional[Tuple[torch.Tensor, ...]]):
@@ -216,12 +217,14 @@ class DecodeState:
         self.shape = make_shape(cfg, T_cap=T_cap, N_cap=self.N_cap)
         Tq = cfg.Tq if Tq is None else Tq
         full = make_shape(cfg, T=T_cap, T_cap=T_cap, N_cap=self.N_cap)
-        nbytes = max(workspace_bytes(OP_LSTM_GATE, full, self.N_cap),
-                     workspace_bytes(OP_GATED_ATTENTION, full, Tq, self.k_cap),
+        # the gate's scratch, and the attention calls' own (their tickets must stay zero between calls, so it is
+        # never lent to the gate)
+        self.ws = alloc_workspace(workspace_bytes(OP_LSTM_GATE, full, self.N_cap), dev)
+        nbytes = max(workspace_bytes(OP_GATED_ATTENTION, full, Tq, self.k_cap),
                      workspace_bytes(OP_DENSE_ATTENTION, full, Tq),
                      max(workspace_bytes(OP_GATED_ATTENTION, make_shape(cfg, T=t, T_cap=T_cap, N_cap=self.N_cap),
                                          Tq, self.k_cap) for t in {cfg.T, min(T_cap, cfg.W + cfg.C)}))
-        self.ws = alloc_workspace(nbytes, dev)
+        self.ws_attn = alloc_workspace(nbytes, dev)
 
 
 def mlp_weights(w: Dict[str, torch.Tensor], kv: str):
@@ -246,4 +249,4 @@ def cold_step(st: DecodeState, t: Dict[str, torch.Tensor], O: torch.Tensor, T: O
     kvev_lstm_gate(sh, st.Kbar, st.Vbar, lstm_weights(t), 0, N, st.h, st.c, st.util, st.gate, st.ws)
     kvev_select(sh, st.util, st.gate, SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)
     kvev_gated_attention(sh, t["Q"], t["Q"].shape[3], t["K"], t["V"], st.Kbar, st.Vbar, st.idx, st.count,
-                         st.k_cap, O, st.ws)
+                         st.k_cap, O, st.ws_attn)

@@ -42,9 +42,12 @@ static int n_cand_of(const kvev_shape *sh) { return (sh->T > sh->W ? sh->T - sh-
 
 // ---- attention planning ---------------------------------------------------
 // Rows are split across workgroups until the launch has a few workgroups per
-// compute unit; a split never gets fewer than a few hundred rows, below which
-// the second (combine) launch costs more than the extra parallelism returns.
-struct AttnPlan { int nsplit, rows_per_split; size_t ws_bytes; };
+// compute unit; the splits of a query are merged inside the same launch (the
+// last workgroup to arrive does it), so a split only has to be worth a
+// workgroup's own start-up: one or two rounds of row loads.
+// Scratch: one ticket (int32) per (key-value sequence, query group), padded to
+// 256 bytes, then the split partials.
+struct AttnPlan { int nsplit, rows_per_split; size_t ticket_bytes, ws_bytes; };
 
 static int env_int(const char *name, int dflt)
 {
@@ -54,7 +57,7 @@ static int env_int(const char *name, int dflt)
 // tuning knobs (environment, read once): workgroups wanted per launch and the
 // smallest split worth a workgroup
 static const int g_attn_target_blocks = env_int("KVEV_ATTN_TARGET_BLOCKS", 1024);
-static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", 512);
+static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", 128);
 
 static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 {
@@ -73,7 +76,8 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
     if (rps < 16) rps = 16;
     p.rows_per_split = rps;
     p.nsplit = n_rows > 0 ? (n_rows + rps - 1) / rps : 1;
-    p.ws_bytes = p.nsplit > 1 ? (size_t)sq * p.nsplit * (sh->d + 2) * sizeof(float) : 0;
+    p.ticket_bytes = ((size_t)units * sizeof(int32_t) + 255) / 256 * 256;
+    p.ws_bytes = p.nsplit > 1 ? p.ticket_bytes + (size_t)sq * p.nsplit * (sh->d + 2) * sizeof(float) : 0;
     return p;
 }
 
@@ -109,12 +113,13 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     if (causal && Tq > sh->T - win0) return KVEV_ERR_INVALID_ARG;      // the frame must lie inside the raw rows
     // a frame of queries on bf16 storage goes to the matrix-core kernel (no split, no scratch)
     const bool mq = attn_takes_mq(sh, Tq);
-    const AttnPlan p = mq ? AttnPlan{1, n_rows, 0} : plan_attn(sh, Tq, n_rows);
+    const AttnPlan p = mq ? AttnPlan{1, n_rows, 0, 0} : plan_attn(sh, Tq, sh->T - win0);     // (split by the raw rows)
     if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes || !aligned16(ws))) return KVEV_ERR_WORKSPACE;
 
     AttnArgs a;
     a.Q = Q; a.K = K; a.V = V; a.Kbar = Kbar; a.Vbar = Vbar; a.idx = idx; a.count = count; a.O = O;
-    a.part = p.nsplit > 1 ? static_cast<float *>(ws) : nullptr;
+    a.tickets = p.nsplit > 1 ? static_cast<int32_t *>(ws) : nullptr;
+    a.part = p.nsplit > 1 ? reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + p.ticket_bytes) : nullptr;
     a.S = sh->L * sh->B * kv_heads(sh); a.Tq = Tq; a.d = sh->d;
     a.G = sh->H / kv_heads(sh); a.Hkv = kv_heads(sh); a.causal = causal;
     a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = compact ? k_cap : sh->N_cap; a.k_cap = k_cap;
@@ -349,13 +354,14 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
         if (k_cap < 0) return 0;
         const int ncand = n_cand_of(sh);
         const int kmax = k_cap < ncand ? k_cap : ncand;
-        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, kmax + sh->T - ncand * sh->C).ws_bytes;
+        (void)kmax;
+        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, sh->T - ncand * sh->C).ws_bytes;
     }
     case KVEV_OP_DENSE_ATTENTION:
         return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, sh->T).ws_bytes;
     case KVEV_OP_COMPACT_ATTENTION:
         if (k_cap < 0) return 0;
-        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, k_cap + sh->T).ws_bytes;
+        return attn_takes_mq(sh, n) ? 0 : plan_attn(sh, n, sh->T).ws_bytes;
     default:
         return 0;
     }
@@ -375,6 +381,6 @@ const char *kvev_status_string(int status)
 
 const char *kvev_last_hip_error(void) { return g_hip_err; }
 
-int kvev_version(void) { return 100; }
+int kvev_version(void) { return 200; }
 
 }  // extern "C"

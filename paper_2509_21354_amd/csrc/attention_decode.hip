@@ -8,9 +8,13 @@
 // covers 4 consecutive rows per load instruction and a workgroup 16, so every
 // wave-level load is one contiguous 1 KiB piece of the cache.  Each lane group
 // keeps its own online-softmax state (m, l, o); the groups are merged by
-// shuffles, the waves through LDS, and the splits of one sequence by a second,
-// deterministic kernel (no float atomics).  A workgroup serves up to 4 queries
-// that share the rows (the heads of a grouped-query group, a short frame).
+// shuffles, the waves through LDS, and the splits of one sequence inside the
+// same launch: every split leaves its partial (o, m, l) in scratch and draws an
+// integer ticket; the workgroup that draws the last one merges all partials in
+// split order (so the result does not depend on who arrives when, and no float
+// atomics are involved) and puts the ticket back to zero.  A workgroup serves up
+// to 4 queries that share the rows (the heads of a grouped-query group, a short
+// frame).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -53,8 +57,11 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
     int cnt = 0;
     if (a.gated) cnt = min(max(a.count[s], 0), a.k_cap);
     const int n = cnt + (a.T - a.win0);
-    const int j0 = split * a.rows_per_split;
-    const int j1 = min(n, j0 + a.rows_per_split);
+    // The raw rows are cut into nsplit runs of rows_per_split; the kept summaries go with the first run.  The cut thus
+    // depends on the raw rows alone, and the compact form (same raw rows, another capacity for the summaries) walks
+    // and merges exactly as the indexed form does.
+    const int j0 = split == 0 ? 0 : cnt + split * a.rows_per_split;
+    const int j1 = min(n, cnt + (split + 1) * a.rows_per_split);
 
     // per query: its row in Q / O and the first row it must not see (causal frame: the
     // queries are the last Tq cached tokens and see nothing after their own position)
@@ -199,54 +206,38 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
             }
         }
     }
-}
+    if (a.nsplit == 1) return;
 
-// Merge of the split partials (o[D], m, l) of one (sequence, query): a
-// log-sum-exp combination in a fixed order (tree over lanes, then waves).  The
-// splits' maxima and sums are reduced across the workgroup first, so that the
-// D-wide accumulation only issues independent loads.
-template <typename T, int D>
-__global__ __launch_bounds__(D) void attn_combine_kernel(AttnArgs a, const float *part, int nsplit, T *O)
-{
-    extern __shared__ float s_w[];                 // [nsplit] weights exp2(m_i - M)
-    __shared__ float s_red[2][D / 64];
-    const int sq = blockIdx.x, t = threadIdx.x, wave = t >> 6;
-    const float *p = part + (size_t)sq * nsplit * (D + 2);
-    float mloc = kNegBig;
-    for (int i = t; i < nsplit; i += D) mloc = fmaxf(mloc, p[(size_t)i * (D + 2) + D]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
-    if ((t & 63) == 0) s_red[0][wave] = mloc;
+    // ---- the splits of these queries meet here: the last one to arrive merges them all ----
+    // Every thread makes its partial visible to the device before the workgroup draws its ticket; the
+    // workgroup that draws number nsplit - 1 knows that all partials are in memory, and reads them after a
+    // fence of its own.  The merge walks the splits in their own order, whoever arrived last.
+    __shared__ int s_last;
+    __threadfence();
     __syncthreads();
-    float M = s_red[0][0];
-#pragma unroll
-    for (int w = 1; w < D / 64; ++w) M = fmaxf(M, s_red[0][w]);
-    float lloc = 0.f;
-    for (int i = t; i < nsplit; i += D) {
-        const float *pi = p + (size_t)i * (D + 2);
-        const float f = exp2f(pi[D] - M);
-        s_w[i] = f;
-        lloc += pi[D + 1] * f;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) lloc += __shfl_xor(lloc, off);
-    if ((t & 63) == 0) s_red[1][wave] = lloc;
+    int32_t *ticket = a.tickets + ((size_t)s * qgroups + qg);
+    if (tid == 0)
+        s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == a.nsplit - 1;
     __syncthreads();
-    float L = s_red[1][0];
-#pragma unroll
-    for (int w = 1; w < D / 64; ++w) L += s_red[1][w];
-    float acc = 0.f;
-    int i = 0;
-    for (; i + 8 <= nsplit; i += 8) {
-        float v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = p[(size_t)(i + u) * (D + 2) + t];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc = fmaf(v[u], s_w[i + u], acc);
+    if (!s_last) return;
+    __threadfence();
+    const int t = tid % D;
+    for (int i = tid / D; i < NQ; i += 64 * NW / D) {
+        const int r = qg * NQ + i;
+        if (r >= R) break;
+        const float *p = a.part + ((size_t)s * R + r) * a.nsplit * (D + 2);
+        float M = kNegBig;
+        for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, p[(size_t)sp * (D + 2) + D]);
+        float L = 0.f, acc = 0.f;
+        for (int sp = 0; sp < a.nsplit; ++sp) {
+            const float *ps = p + (size_t)sp * (D + 2);
+            const float f = exp2f(ps[D] - M);
+            L = fmaf(ps[D + 1], f, L);
+            acc = fmaf(ps[t], f, acc);
+        }
+        Storage<T>::store(static_cast<T *>(a.O) + query_row(a, s, r) * D + t, L > 0.f ? acc / L : 0.f);
     }
-    for (; i < nsplit; ++i) acc = fmaf(p[(size_t)i * (D + 2) + t], s_w[i], acc);
-    const int R = a.G * a.Tq;
-    Storage<T>::store(O + query_row(a, sq / R, sq % R) * D + t, L > 0.f ? acc / L : 0.f);
+    if (tid == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
 }
 
 template <typename T, int D, int NQ>
@@ -260,9 +251,6 @@ static hipError_t launch_decode_q(const AttnArgs &a, hipStream_t st)
         hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 16>), dim3((unsigned)blocks), dim3(1024), 0, st, a);
     else
         hipLaunchKernelGGL((attn_decode_kernel<T, D, U, NQ, 4>), dim3((unsigned)blocks), dim3(256), 0, st, a);
-    if (a.nsplit > 1)
-        hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3((unsigned)((size_t)a.S * R)), dim3(D),
-                           (size_t)a.nsplit * sizeof(float), st, a, a.part, a.nsplit, static_cast<T *>(a.O));
     return hipGetLastError();
 }
 

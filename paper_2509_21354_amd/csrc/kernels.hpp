@@ -12,6 +12,7 @@ struct AttnArgs {
     const int32_t *idx, *count;
     void *O;
     float *part;          // split partials [S*Tq][nsplit][d+2] (o, m, l), or null when nsplit == 1
+    int32_t *tickets;     // one arrival counter per (key-value sequence, query group), zero between calls; null when nsplit == 1
     int S, Tq, d;          // S: key-value sequences (L*B*H_kv)
     int G, Hkv;           // query heads per key-value head; key-value heads per (layer, batch row)
     int causal;           // 1: the Tq queries are the last Tq cached tokens and see nothing after themselves

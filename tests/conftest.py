@@ -17,3 +17,12 @@ def oracle():
     from oracle import kvev_oracle
     kvev_oracle.build()
     return kvev_oracle
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Parity figures the tests measured (kept-index comparison, worst errors): printed at any verbosity."""
+    from tests import helpers
+    if helpers.REPORTS:
+        terminalreporter.section("parity report")
+        for line in helpers.REPORTS:
+            terminalreporter.write_line(line)

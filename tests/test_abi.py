@@ -149,3 +149,4 @@ def test_retain_and_compact_attention_validation():
     assert L.kvev_compact_attention(r, FAKE, 1, FAKE, FAKE, sh.T_cap, FAKE, FAKE, FAKE, 32, 0, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
     assert L.kvev_compact_attention(r, FAKE, 5000, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 32, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # frame longer than the window
 
+

@@ -123,7 +123,7 @@ def test_compact_attention_gives_the_bits_of_the_indexed_attention(number, Tq):
     # a causal frame (the queries are the window's last Tq tokens): same bits as the indexed causal form, and the oracle's values
     if Tq > 1:
         O3, O4 = torch.empty_like(O), torch.empty_like(O)
-        kb.kvev_gated_attention(st.shape, g["Q"], Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, O3, st.ws, causal=1)
+        kb.kvev_gated_attention(st.shape, g["Q"], Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, O3, st.ws_attn, causal=1)
         kb.kvev_compact_attention(shw, g["Q"], Tq, Kw, Vw, Kc, Vc, cnt, k_cap, O4, ws, causal=1)
         torch.cuda.synchronize()
         assert (_bits(O4) == _bits(O3)).all() and not (_bits(O4) == _bits(O2)).all()
@@ -166,7 +166,7 @@ def test_evicting_stream_equals_the_full_cache_stream():
                           full.ws)
         kb.kvev_select(sh, full.util, full.gate, kb.SELECT_TOPK, cfg.k, 0.0, full.k_cap, full.idx, full.count)
         kb.kvev_gated_attention(sh, g["Q"], 1, g["K"], g["V"], full.Kbar, full.Vbar, full.idx, full.count, full.k_cap,
-                                O1, full.ws)
+                                O1, full.ws_attn)
         # ---- evicting path: chunks that left the window this frame enter the store, the window is rebased
         n_in = n_cand - ncand_old
         if n_in > 0:

@@ -47,10 +47,10 @@ def test_chain_and_attention_with_grouped_heads_and_causal_frames(cfg, causal):
     kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, kb.lstm_weights(g), 0, N, st.h, st.c, st.util, st.gate, st.ws)
     kb.kvev_select(sh, st.util, st.gate, kb.SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)
     O = torch.empty_like(g["Q"])
-    kb.kvev_gated_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, O, st.ws,
+    kb.kvev_gated_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, O, st.ws_attn,
                             causal=causal)
     Od = torch.empty_like(g["Q"])
-    kb.kvev_dense_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], Od, st.ws, causal=causal)
+    kb.kvev_dense_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], Od, st.ws_attn, causal=causal)
     torch.cuda.synchronize()
     # the chain per key-value head against the oracle's stages
     rK, rV = orc.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, st.N_cap, cfg.d_sum, orc.POOL_MLP,
@@ -93,7 +93,7 @@ def test_chain_and_attention_with_grouped_heads_and_causal_frames(cfg, causal):
         # the last query of a causal frame sees everything: same bits as the frame without the mask
         On = torch.empty_like(O)
         kb.kvev_gated_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, st.k_cap, On,
-                                st.ws, causal=0)
+                                st.ws_attn, causal=0)
         torch.cuda.synchronize()
         assert (orc.to_np(On)[..., -1, :] == orc.to_np(O)[..., -1, :]).all()
         assert not (orc.to_np(On)[..., 0, :] == orc.to_np(O)[..., 0, :]).all()
@@ -107,12 +107,12 @@ def test_grouped_heads_read_the_rows_once_per_group():
     g = dev(t)
     st = kb.DecodeState(cfg)
     O = torch.empty_like(g["Q"])
-    kb.kvev_dense_attention(st.shape, g["Q"], 1, g["K"], g["V"], O, st.ws)
+    kb.kvev_dense_attention(st.shape, g["Q"], 1, g["K"], g["V"], O, st.ws_attn)
     G = cfg.H // cfg.H_kv
     full = cfg.replace(H_kv=0)
     st2 = kb.DecodeState(full)
     K2, V2 = g["K"].repeat_interleave(G, dim=2).contiguous(), g["V"].repeat_interleave(G, dim=2).contiguous()
     O2 = torch.empty_like(O)
-    kb.kvev_dense_attention(st2.shape, g["Q"], 1, K2, V2, O2, st2.ws)
+    kb.kvev_dense_attention(st2.shape, g["Q"], 1, K2, V2, O2, st2.ws_attn)
     torch.cuda.synchronize()
     assert_close_storage(O, orc.to_np(O2), cfg.dtype, "grouped vs repeated heads")

@@ -101,7 +101,7 @@ def test_config3_full_size_sampled():
     gw = dict(g)
     gw.update(w)
     kb.cold_step(st, gw, O)
-    kb.kvev_dense_attention(st.shape, g["Q"], cfg.Tq, g["K"], g["V"], D, st.ws)
+    kb.kvev_dense_attention(st.shape, g["Q"], cfg.Tq, g["K"], g["V"], D, st.ws_attn)
     torch.cuda.synchronize()
     print("\n[cfg3] GPU done", flush=True)
     _select_all(cfg, st, cfg.T)
@@ -140,7 +140,7 @@ def test_config4_streaming_full_size_sampled():
         for i in range(cfg.decode_per_step):
             O = torch.empty_like(Qs[s, i])
             kb.kvev_gated_attention(sh, Qs[s, i], 1, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count,
-                                    st.k_cap, O, st.ws)
+                                    st.k_cap, O, st.ws_attn)
             outs.append(O)
         if s in checks:
             torch.cuda.synchronize()
@@ -182,7 +182,7 @@ def test_config5_multiquery_full_size_sampled():
     gw = dict(g)
     gw.update(w)
     kb.cold_step(st, gw, O)
-    kb.kvev_dense_attention(st.shape, g["Q"], cfg.Tq, g["K"], g["V"], D, st.ws)
+    kb.kvev_dense_attention(st.shape, g["Q"], cfg.Tq, g["K"], g["V"], D, st.ws_attn)
     torch.cuda.synchronize()
     print("\n[cfg5] GPU done", flush=True)
     _select_all(cfg, st, cfg.T)

@@ -13,7 +13,7 @@ import torch
 from oracle import kvev_oracle as orc
 from paper_2509_21354_amd import binding as kb
 from paper_2509_21354_amd import synth
-from tests.helpers import assert_close_storage, bf16_ulp_mismatch, dev, index_report, vals
+from tests.helpers import assert_close_storage, bf16_ulp_mismatch, dev, index_protocol, report, vals
 
 pytestmark = pytest.mark.gpu
 
@@ -314,23 +314,18 @@ def test_cold_step_end_to_end(number):
     r = orc.cold_step(t["Q"], t["K"], t["V"], t, cfg.T, cfg.C, cfg.W, cfg.k, cfg.d_sum)
     assert_close_storage(st.Kbar, r["Kbar"], cfg.dtype, "Kbar")
     assert_close_storage(st.Vbar, r["Vbar"], cfg.dtype, "Vbar")
-    S, bad, worst, details = index_report(st.idx, st.count, r["idx"], r["count"], r["util"])
     du = np.abs(st.util.cpu().numpy() - r["util"]).max()
-    print(f"\n[{cfg.name}] sequences={S} index-mismatching={bad} worst oracle gap={worst:.3e} "
-          f"max |util_gpu-util_oracle|={du:.3e}")
-    for d in details[:8]:
-        print("   mismatch:", d)
+    frac, ulp = bf16_ulp_mismatch(st.Kbar, r["Kbar"])
+    report(f"[{cfg.name}] end to end: max |util_gpu - util_oracle| = {du:.3e}; stored summaries differing from the "
+           f"oracle's: {frac:.2e} of elements, at most {ulp:.2f} ulp")
     if cfg.dtype == "f32":
         assert du <= SCORE_TOL
-        assert bad == 0 or worst <= 1e-6, details
     else:
-        # a 1-ulp bf16 flip of a stored summary moves later scores by ~1e-4..1e-3: chunks whose
-        # utilities are closer than that may swap; anything wider is a failure
-        frac, ulp = bf16_ulp_mismatch(st.Kbar, r["Kbar"])
-        print(f"   bf16 summary flips: {frac:.2e} of elements, max {ulp} ulp")
-        assert ulp <= 1
-        assert worst <= 5e-3, details
-        assert bad <= max(1, S // 4)
+        assert ulp <= 1.01
+    # kept indices: identical, or a tie within 1e-6 (reported), or traced to a stored-summary rounding; else failure
+    rec = index_protocol(cfg.name, st.idx, st.count, r, st.Kbar.cpu(), st.Vbar.cpu(), kb.lstm_weights(t),
+                         cfg.T, cfg.C, cfg.W, cfg.k, st.k_cap)
+    S = rec["sequences"]
     same = (orc.to_np(st.idx) == r["idx"]).reshape(S, -1).all(axis=1)
     Og, Or = vals(O).reshape(S, -1), vals(r["O"]).reshape(S, -1)
     if same.any():
@@ -365,7 +360,7 @@ def test_threshold_step_end_to_end():
     tau = float(np.quantile(gate[..., :n_cand], 1.0 - 0.687))
     kb.kvev_select(sh, None, st.gate, kb.SELECT_THRESHOLD, 0, tau, n_cand, st.idx, st.count)
     O = torch.empty_like(g["Q"])
-    kb.kvev_gated_attention(sh, g["Q"], 1, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, n_cand, O, st.ws)
+    kb.kvev_gated_attention(sh, g["Q"], 1, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count, n_cand, O, st.ws_attn)
     torch.cuda.synchronize()
     ridx, rcnt = orc.select_threshold(gate, cfg.T, cfg.C, cfg.W, tau, n_cand)
     cnt = orc.to_np(st.count)
@@ -417,7 +412,7 @@ def test_streaming_matches_oracle_and_cold_recompute():
         for i in range(cfg.decode_per_step):
             O = torch.empty_like(gQs[s, i])
             kb.kvev_gated_attention(sh, gQs[s, i], 1, g["K"], g["V"], st.Kbar, st.Vbar, st.idx, st.count,
-                                    st.k_cap, O, st.ws)
+                                    st.k_cap, O, st.ws_attn)
             torch.cuda.synchronize()
             want = orc.gated_attention(Qs[s, i], t["K"], t["V"], st.Kbar.cpu(), st.Vbar.cpu(), st.idx.cpu(),
                                        st.count.cpu(), T, cfg.C, cfg.W)
