@@ -37,7 +37,7 @@ extern "C" {
 #endif
 
 enum { KVEV_OK = 0, KVEV_ERR_INVALID_ARG = 1, KVEV_ERR_UNSUPPORTED = 2, KVEV_ERR_WORKSPACE = 3,
-       KVEV_ERR_HIP = 4 };
+       KVEV_ERR_HIP = 4, KVEV_ERR_STATIC_SCRATCH = 5 };
 enum { KVEV_F32 = 0, KVEV_BF16 = 1 };           /* storage type of Q/K/V, summaries, weights */
 enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1, KVEV_POOL_MAX = 2, KVEV_POOL_TOKEN_MLP = 3 };
 enum { KVEV_SELECT_TOPK = 0, KVEV_SELECT_THRESHOLD = 1 };
@@ -159,6 +159,24 @@ int kvev_gated_attention(const kvev_shape *shape, const void *Q, int Tq, const v
                          const void *V, const void *Kbar, const void *Vbar, const int32_t *idx,
                          const int32_t *count, int k_cap, int causal, void *O, void *ws,
                          size_t ws_bytes, void *stream);
+
+/* kvev_gated_attention for callers that cannot allocate device memory or carry a
+ * scratch buffer of their own: code recorded into a HIP graph, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, arithmetic and
+ * results as kvev_gated_attention, minus the workspace: the split partials and
+ * tickets live in an array of KVEV_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (one copy per GPU, held until the process ends).  The
+ * call allocates nothing and frees nothing.  Every call on a GPU uses that
+ * GPU's one array, whatever its stream: calls that may overlap in time on one
+ * GPU race and must be ordered by the caller.  The first call on a device looks
+ * up the array's address (not a stream operation: make that first call outside
+ * stream capture).  Errors as kvev_gated_attention, and KVEV_ERR_STATIC_SCRATCH
+ * when the shape wants more scratch than the array holds
+ * (kvev_workspace_bytes(KVEV_OP_GATED_ATTENTION, ...) tells how much). */
+#define KVEV_STATIC_SCRATCH_BYTES (4u << 20)
+int kvev_gated_attention_static(const kvev_shape *shape, const void *Q, int Tq, const void *K,
+                                const void *V, const void *Kbar, const void *Vbar, const int32_t *idx,
+                                const int32_t *count, int k_cap, int causal, void *O, void *stream);
 
 /* Eq. 1 over the whole cache, tokens 0 .. T-1: the baseline whose O(n) cost
  * per new token the method removes (section 2, "Transformer Attention").

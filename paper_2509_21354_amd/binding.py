@@ -18,14 +18,15 @@ from . import synth
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvev.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_STATIC_SCRATCH = range(6)
+STATIC_SCRATCH_BYTES = 4 << 20
 F32, BF16 = 0, 1
 POOL_MEAN, POOL_MLP, POOL_MAX, POOL_TOKEN_MLP = 0, 1, 2, 3
 SELECT_TOPK, SELECT_THRESHOLD = 0, 1
 OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, OP_COMPACT_ATTENTION = range(6)
 
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
-           "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
+           "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
            "kvev_status_string", "kvev_last_hip_error", "kvev_version", "kvev_debug_pair_wait")
 
 
@@ -67,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.kvev_lstm_gate.argtypes = [shp, vp, vp, ctypes.POINTER(LstmW), ci, ci, vp, vp, vp, vp, vp, sz, vp]
         L.kvev_select.argtypes = [shp, vp, vp, ci, ci, ctypes.c_float, ci, vp, vp, vp]
         L.kvev_gated_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]
+        L.kvev_gated_attention_static.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp]
         L.kvev_dense_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, sz, vp]
         L.kvev_retain.argtypes = [shp, ci, ci, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, vp, ci, ci, vp, vp, sz, vp]
@@ -78,7 +80,7 @@ def lib() -> ctypes.CDLL:
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
         for n in ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
-                  "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_version"):
+                  "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_version"):
             getattr(L, n).restype = ci
         _lib = L
     return _lib
@@ -171,6 +173,12 @@ def kvev_gated_attention(shape: Shape, Q, Tq, K, V, Kbar, Vbar, idx, count, k_ca
                                     _ptr(Vbar), _ptr(idx), _ptr(count), k_cap, causal, _ptr(O), _ptr(ws),
                                     ws.numel() if ws is not None else 0, _stream())
     _check(st, "kvev_gated_attention")
+
+
+def kvev_gated_attention_static(shape: Shape, Q, Tq, K, V, Kbar, Vbar, idx, count, k_cap, O, causal=0):
+    st = lib().kvev_gated_attention_static(ctypes.byref(shape), _ptr(Q), Tq, _ptr(K), _ptr(V), _ptr(Kbar),
+                                           _ptr(Vbar), _ptr(idx), _ptr(count), k_cap, causal, _ptr(O), _stream())
+    _check(st, "kvev_gated_attention_static")
 
 
 def kvev_dense_attention(shape: Shape, Q, Tq, K, V, O, ws=None, causal=0):

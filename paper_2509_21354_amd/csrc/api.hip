@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -87,10 +89,45 @@ static bool attn_takes_mq(const kvev_shape *sh, int Tq)
     return sh->dtype == KVEV_BF16 && (int64_t)(sh->H / kv_heads(sh)) * Tq >= 16;
 }
 
+// ---- scratch that the library holds itself (kvev_gated_attention_static) ----
+// One array per GPU, there from the moment the code object is loaded until the process ends.  `scratch` names it for
+// the device code only: host code reaches its memory through the address that hipGetSymbolAddress reports for the
+// current device, looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = KVEV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on device i, or null: not looked up yet
+
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return KVEV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVEV_OK;
+}
+
+// zeroes n16 16-byte words (a kernel, not hipMemsetAsync: the call may be recorded into a HIP graph)
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *p, size_t n16)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
                             const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
                             int k_cap, int gated, int causal, void *O, void *ws, size_t ws_bytes,
-                            void *stream, int ring_first = 0)
+                            void *stream, int ring_first = 0, bool static_ws = false)
 {
     int rc = check_shape(sh, gated != 2);     // a compact store has no chunk grid over the raw buffer
     if (rc) return rc;
@@ -114,6 +151,19 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     // a frame of queries on bf16 storage goes to the matrix-core kernel (no split, no scratch)
     const bool mq = attn_takes_mq(sh, Tq);
     const AttnPlan p = mq ? AttnPlan{1, n_rows, 0, 0} : plan_attn(sh, Tq, sh->T - win0);     // (split by the raw rows)
+    if (static_ws) {
+        // the library's own array stands in for the caller's scratch; its tickets are cleared on every call, so
+        // nothing is assumed about what the call before left there
+        if (p.ws_bytes > kStaticScratchBytes) return KVEV_ERR_STATIC_SCRATCH;
+        if (p.ws_bytes > 0) {
+            rc = static_scratch(&ws);
+            if (rc) return rc;
+            ws_bytes = kStaticScratchBytes;
+            const size_t n16 = p.ticket_bytes / 16;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), static_cast<uint4 *>(ws), n16);
+        }
+    }
     if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes || !aligned16(ws))) return KVEV_ERR_WORKSPACE;
 
     AttnArgs a;
@@ -295,6 +345,13 @@ int kvev_gated_attention(const kvev_shape *sh, const void *Q, int Tq, const void
     return attention_common(sh, Q, Tq, K, V, Kbar, Vbar, idx, count, k_cap, 1, causal, O, ws, ws_bytes, stream);
 }
 
+int kvev_gated_attention_static(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V,
+                                const void *Kbar, const void *Vbar, const int32_t *idx, const int32_t *count,
+                                int k_cap, int causal, void *O, void *stream)
+{
+    return attention_common(sh, Q, Tq, K, V, Kbar, Vbar, idx, count, k_cap, 1, causal, O, nullptr, 0, stream, 0, true);
+}
+
 int kvev_dense_attention(const kvev_shape *sh, const void *Q, int Tq, const void *K, const void *V, int causal,
                          void *O, void *ws, size_t ws_bytes, void *stream)
 {
@@ -375,6 +432,7 @@ const char *kvev_status_string(int status)
     case KVEV_ERR_UNSUPPORTED: return "unsupported shape, dtype or mode";
     case KVEV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case KVEV_ERR_HIP: return "HIP runtime error";
+    case KVEV_ERR_STATIC_SCRATCH: return "the shape needs more scratch than the library's static array holds";
     default: return "unknown status";
     }
 }

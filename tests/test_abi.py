@@ -150,3 +150,30 @@ def test_retain_and_compact_attention_validation():
     assert L.kvev_compact_attention(r, FAKE, 5000, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 32, 1, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # frame longer than the window
 
 
+
+def test_static_scratch_entry_validates_and_rejects_oversized_shapes():
+    """kvev_gated_attention_static: the usual validation, and a shape whose split scratch would not fit the
+    library's array is refused before any GPU call.  With the default planning no shape needs more than the array
+    holds, so the refusal is provoked in a child process that asks for far more workgroups per launch."""
+    import subprocess
+    import sys
+    L = kb.lib()
+    sh = _shape()
+    r = ctypes.byref(sh)
+    assert L.kvev_gated_attention_static(r, None, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 0, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_gated_attention_static(r, FAKE, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, 0, FAKE, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_gated_attention_static(r, FAKE, 0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 32, 0, FAKE, None) == kb.OK
+    assert b"static" in L.kvev_status_string(kb.ERR_STATIC_SCRATCH)
+    code = (
+        "import ctypes\n"
+        "from paper_2509_21354_amd import binding as kb, synth\n"
+        "L = kb.lib()\n"
+        "sh = kb.make_shape(synth.CONFIGS[2], T=131072, T_cap=131072, N_cap=4096, W=131072)\n"
+        "F = ctypes.c_void_p(0x1000)\n"
+        "need = kb.workspace_bytes(kb.OP_GATED_ATTENTION, sh, 1, 32)\n"
+        "assert need > kb.STATIC_SCRATCH_BYTES, need\n"
+        "rc = L.kvev_gated_attention_static(ctypes.byref(sh), F, 1, F, F, F, F, F, F, 32, 0, F, None)\n"
+        "assert rc == kb.ERR_STATIC_SCRATCH, rc\n")
+    env = dict(os.environ, KVEV_ATTN_TARGET_BLOCKS="65536", KVEV_ATTN_MIN_ROWS="64", PYTHONPATH=ROOT)
+    res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, cwd=ROOT)
+    assert res.returncode == 0, res.stderr
