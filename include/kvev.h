@@ -229,20 +229,6 @@ int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const
  * arguments are invalid. */
 size_t kvev_workspace_bytes(int op, const kvev_shape *shape, int n, int k_cap);
 
-/* For tests of the gate's failure path, not for production use.  Small launches
- * of kvev_lstm_gate run a group of sequences on two workgroups that wait for
- * each other's data (see there).  This sets, for later calls in this process,
- * the number of polls one such wait may take (default 1 << 22) and the member
- * (0 or 1; -1 = none, the default) that withholds what it would publish, so
- * that its partner's wait expires: every kernel still ends normally and the
- * affected launch's util, gate and c come back NaN.  write_through = 1 makes
- * the two workgroups publish with device-scope (write-through) stores even
- * when they share an L2 and plain stores would do: the path taken when they
- * do not.  Results are the same bits either way.  Not thread-safe.
- * Errors: INVALID_ARG for spin_limit < 1, a member outside -1..1 or
- * write_through outside 0..1. */
-int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through);
-
 /* Static description of a status code. */
 const char *kvev_status_string(int status);
 

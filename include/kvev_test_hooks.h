@@ -1,0 +1,37 @@
+/*
+ * kvev test hooks: entry points that exist for the tests of the library, not for
+ * its users.  They change process-wide settings (atomically; a call that is
+ * already being planned may see the old or the new value) and are declared here,
+ * apart from kvev.h, so that nothing in the public interface depends on them.
+ */
+#ifndef KVEV_TEST_HOOKS_H
+#define KVEV_TEST_HOOKS_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* For tests of the gate's failure path.  Small launches
+ * of kvev_lstm_gate run a group of sequences on two workgroups that wait for
+ * each other's data (see there).  This sets, for later calls in this process,
+ * the number of polls one such wait may take (default 1 << 22) and the member
+ * (0 or 1; -1 = none, the default) that withholds what it would publish, so
+ * that its partner's wait expires: every kernel still ends normally and the
+ * affected launch's util, gate and c come back NaN.  write_through = 1 makes
+ * the two workgroups publish with device-scope (write-through) stores even
+ * when they share an L2 and plain stores would do: the path taken when they
+ * do not.  Results are the same bits either way.   Errors: INVALID_ARG for spin_limit < 1, a member outside -1..1 or
+ * write_through outside 0..1. */
+int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through);
+
+/* For parity tests of the single-kernel form of the gate (bf16, d_g = 256), which the
+ * library takes for launches of at least `min_groups` groups of 16 sequences
+ * (default 257: more than one group per compute unit).  Lowering it lets a test
+ * run that form on a shape the CPU oracle finishes in seconds; 0 restores the
+ * default.  Errors: INVALID_ARG for a negative value. */
+int kvev_debug_lstm_fused_min_groups(int min_groups);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVEV_TEST_HOOKS_H */

@@ -27,7 +27,8 @@ OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, 
 
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
            "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
-           "kvev_status_string", "kvev_last_hip_error", "kvev_version", "kvev_debug_pair_wait")
+           "kvev_status_string", "kvev_last_hip_error", "kvev_version")
+TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups")      # include/kvev_test_hooks.h
 
 
 class Shape(ctypes.Structure):
@@ -76,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_workspace_bytes.restype = sz
         L.kvev_debug_pair_wait.argtypes = [ci, ci, ci]
         L.kvev_debug_pair_wait.restype = ci
+        L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
+        L.kvev_debug_lstm_fused_min_groups.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
@@ -130,6 +133,10 @@ def make_shape(cfg=None, **kw) -> Shape:
 
 def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1, write_through: int = 0) -> None:
     _check(lib().kvev_debug_pair_wait(spin_limit, mute_member, write_through), "kvev_debug_pair_wait")
+
+
+def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:
+    _check(lib().kvev_debug_lstm_fused_min_groups(min_groups), "kvev_debug_lstm_fused_min_groups")
 
 
 def workspace_bytes(op: int, shape: Shape, n: int, k_cap: int = 0) -> int:

@@ -35,7 +35,7 @@ def _headers_mtime():
 
 
 def _compile(src: str, obj: str) -> str:
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *os.environ.get("KVEV_EXTRA_FLAGS", "").split(), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {os.path.basename(src)}:\n{r.stdout}\n{r.stderr}")

@@ -5,8 +5,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
+#include "../../include/kvev_test_hooks.h"
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -56,10 +58,12 @@ static int env_int(const char *name, int dflt)
     const char *v = getenv(name);
     return v && *v ? atoi(v) : dflt;
 }
-// tuning knobs (environment, read once): workgroups wanted per launch and the
-// smallest split worth a workgroup
-static const int g_attn_target_blocks = env_int("KVEV_ATTN_TARGET_BLOCKS", 1024);
-static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", 128);
+// Tuning knobs (environment, read once; unset = the rule below): workgroups wanted per launch and the smallest
+// run of raw rows worth a workgroup.  The rule: with fewer key-value units than compute units the launch is filled
+// with up to one 16-wave workgroup per compute unit and runs down to 64 rows (one batch of a 4-wave workgroup);
+// with more, four 4-wave workgroups per compute unit and runs of at least 512 rows.
+static const int g_attn_target_blocks = env_int("KVEV_ATTN_TARGET_BLOCKS", -1);
+static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", -1);
 
 static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 {
@@ -69,9 +73,13 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
     const int64_t qgroups = R >= 4 ? (R + 3) / 4 : R >= 2 ? (R + 1) / 2 : 1;
     const int64_t units = (int64_t)sh->L * sh->B * kv_heads(sh) * qgroups;
     const int64_t sq = (int64_t)sh->L * sh->B * sh->H * (Tq > 0 ? Tq : 1);
-    int64_t want = (g_attn_target_blocks + units - 1) / units;
-    int64_t most = (n_rows + g_attn_min_rows - 1) / g_attn_min_rows;
+    const bool few = units < 256;
+    const int target = g_attn_target_blocks > 0 ? g_attn_target_blocks : few ? 256 : 1024;
+    const int min_rows = g_attn_min_rows > 0 ? g_attn_min_rows : few ? 64 : 512;
+    int64_t want = (target + units - 1) / units;
+    int64_t most = (n_rows + min_rows - 1) / min_rows;
     if (want > most) want = most;
+    if (want > KVEV_ATTN_MAX_SPLIT) want = KVEV_ATTN_MAX_SPLIT;
     if (want < 1) want = 1;
     int rps = (int)((n_rows + want - 1) / want);
     rps = (rps + 15) / 16 * 16;
@@ -192,11 +200,21 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
 
 // Bound on the polls of one wait of the paired recurrence (each poll is a round trip to memory, about a
 // microsecond: seconds in all), and the member whose publications are withheld; kvev_debug_pair_wait changes them.
-static int g_pair_spin_limit = 1 << 22, g_pair_mute = -1, g_pair_write_through = 0;
+static std::atomic<int> g_pair_spin_limit{1 << 22}, g_pair_mute{-1}, g_pair_write_through{0};
 
 static long long lstm_groups(const kvev_shape *sh)
 {
     return (long long)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
+}
+
+// Launches that give every compute unit a workgroup of 32 sequences take the single-kernel form at d_g = 256
+// (no projections in scratch); smaller ones keep the two-kernel form, whose 16-sequence workgroups (or pairs of
+// them) have the shorter step.  KVEV_LSTM_FUSED_MIN_GROUPS (groups of 16 sequences, read once) moves the border.
+static const int g_lstm_fused_min_groups_default = env_int("KVEV_LSTM_FUSED_MIN_GROUPS", 257);
+static std::atomic<int> g_lstm_fused_min_groups{g_lstm_fused_min_groups_default};
+static bool lstm_takes_fused(const kvev_shape *sh)
+{
+    return lstm_takes_mfma(sh) && sh->d_g == 256 && lstm_groups(sh) >= g_lstm_fused_min_groups.load();
 }
 
 // W_hh and W_ih re-laid in MFMA fragment order sit at the front of the scratch:
@@ -214,7 +232,7 @@ static size_t lstm_ws_pack(const kvev_shape *sh)
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
 {
-    if (!lstm_takes_mfma(sh)) return 0;
+    if (!lstm_takes_mfma(sh) || lstm_takes_fused(sh)) return 0;
     return (size_t)lstm_groups(sh) * 16 * 4 * sh->d_g * sizeof(float);
 }
 
@@ -295,7 +313,8 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
     if (lstm_takes_mfma(sh)) {
         const size_t per = lstm_ws_per_step(sh), pack = lstm_ws_pack(sh);
         if (!ws || !aligned16(ws) || ws_bytes < pack + per) return KVEV_ERR_WORKSPACE;
-        size_t tb = (ws_bytes - pack) / per;
+        a.fused = lstm_takes_fused(sh) ? 1 : 0;
+        size_t tb = a.fused ? (size_t)(chunk_end - chunk_begin) : (ws_bytes - pack) / per;
         if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
         a.tb = (int)tb;
         a.whh_packed = static_cast<const bf16x8_t *>(ws);
@@ -303,9 +322,9 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
         a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) +
                                                 (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
         a.exch_bytes = lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh));
-        a.pair_spin_limit = g_pair_spin_limit;
-        a.pair_mute = g_pair_mute;
-        a.pair_write_through = g_pair_write_through;
+        a.pair_spin_limit = g_pair_spin_limit.load();
+        a.pair_mute = g_pair_mute.load();
+        a.pair_write_through = g_pair_write_through.load();
         a.exch = a.exch_bytes ? static_cast<unsigned char *>(ws) + lstm_ws_weights(sh) : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
@@ -398,6 +417,13 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through)
     return KVEV_OK;
 }
 
+int kvev_debug_lstm_fused_min_groups(int min_groups)
+{
+    if (min_groups < 0) return KVEV_ERR_INVALID_ARG;
+    g_lstm_fused_min_groups = min_groups == 0 ? g_lstm_fused_min_groups_default : min_groups;
+    return KVEV_OK;
+}
+
 size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
 {
     if (check_shape(sh, op != KVEV_OP_COMPACT_ATTENTION) != KVEV_OK || n < 0) return 0;
@@ -405,7 +431,8 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
     case KVEV_OP_LSTM_GATE: {
         const size_t per = lstm_ws_per_step(sh);
         const int tb = n < 128 ? n : 128;
-        return per == 0 ? 0 : lstm_ws_pack(sh) + per * (size_t)(tb < 1 ? 1 : tb);
+        if (!lstm_takes_mfma(sh)) return 0;
+        return lstm_ws_pack(sh) + per * (size_t)(tb < 1 ? 1 : tb);
     }
     case KVEV_OP_GATED_ATTENTION: {
         if (k_cap < 0) return 0;

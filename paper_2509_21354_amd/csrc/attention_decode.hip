@@ -21,6 +21,18 @@
 namespace kvev {
 
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for -inf: exp2(kNegBig - x) == 0, no NaN
+constexpr int kMaxSplit = KVEV_ATTN_MAX_SPLIT;   // most splits per query (the host plans within it)
+
+// Device-scope accesses for what workgroups on different XCDs hand each other: the store writes through the
+// XCD's L2, the load reads past the caches that are not coherent across XCDs.
+__device__ __forceinline__ void store_device(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Queries that share a key-value sequence: the Tq queries of each of the G query
 // heads of its group (grouped-query attention), numbered r = g * Tq + tq.  Row of
@@ -54,17 +66,27 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
     const T *K = static_cast<const T *>(a.K), *V = static_cast<const T *>(a.V);
     const T *Kbar = static_cast<const T *>(a.Kbar), *Vbar = static_cast<const T *>(a.Vbar);
 
-    int cnt = 0;
-    if (a.gated) cnt = min(max(a.count[s], 0), a.k_cap);
-    const int n = cnt + (a.T - a.win0);
     // The raw rows are cut into nsplit runs of rows_per_split; the kept summaries go with the first run.  The cut thus
     // depends on the raw rows alone, and the compact form (same raw rows, another capacity for the summaries) walks
-    // and merges exactly as the indexed form does.
-    const int j0 = split == 0 ? 0 : cnt + split * a.rows_per_split;
-    const int j1 = min(n, cnt + (split + 1) * a.rows_per_split);
+    // and merges exactly as the indexed form does.  A workgroup takes its raw rows first: their addresses need
+    // nothing from memory, so their loads leave together with those of the queries, the kept count and the first
+    // chunk indices, and the summaries (whose addresses come out of the index list) follow one round trip later
+    // instead of two.
+    const int wlen = a.T - a.win0;
+    const int w0 = split * a.rows_per_split;
+    const int w1 = min(wlen, w0 + a.rows_per_split);
+    const int32_t *idx = a.idx ? a.idx + (size_t)s * a.k_cap : nullptr;   // null: the store is compact, row j is entry j
+    int cnt_raw = 0;
+    if (a.gated && split == 0) cnt_raw = a.count[s];
+    int idx0[U];                  // the chunk indices of this lane group's first batch of summaries, asked for early
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int j = grp + GROUPS * u;
+        idx0[u] = a.gated && split == 0 && idx && a.k_cap > 0 ? idx[min(j, a.k_cap - 1)] : j;
+    }
 
-    // per query: its row in Q / O and the first row it must not see (causal frame: the
-    // queries are the last Tq cached tokens and see nothing after their own position)
+    // per query: its row in Q / O and the first raw row it must not see (causal frame: the queries are the
+    // last Tq cached tokens and see nothing after their own position; a summary is older than every raw row)
     float qv[NQ][EPL];
     size_t qrow[NQ];
     int lim[NQ];
@@ -75,7 +97,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
         qok[i] = r < R;
         const int rc = qok[i] ? r : R - 1;
         qrow[i] = query_row(a, s, rc);
-        lim[i] = qok[i] ? (a.causal ? n - (a.Tq - 1 - rc % a.Tq) : n) : 0;
+        lim[i] = qok[i] ? (a.causal ? wlen - (a.Tq - 1 - rc % a.Tq) : wlen) : -1;
         Raw<T, EPL> raw;
         raw.load(static_cast<const T *>(a.Q) + qrow[i] * D + cl * EPL);
         raw.get(qv[i]);
@@ -93,31 +115,11 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
 
     const size_t seq_raw = (size_t)s * a.T_cap;
     const size_t seq_sum = (size_t)s * a.N_cap;
-    const int32_t *idx = a.idx ? a.idx + (size_t)s * a.k_cap : nullptr;   // null: the store is compact, row j is entry j
 
-    for (int base = j0; base < j1; base += GROUPS * U) {
-        Raw<T, EPL> kr[U], vr[U];
-        int jrow[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int j = base + grp + GROUPS * u;
-            jrow[u] = j < j1 ? j : n;          // n: beyond every query's limit
-            j = j < j1 ? j : j1 - 1;
-            size_t off;
-            const T *kb, *vb;
-            if (j < cnt) {
-                int c = min(max(idx ? idx[j] : j, 0), a.N_cap - 1);
-                off = (seq_sum + c) * D;
-                kb = Kbar; vb = Vbar;
-            } else {
-                int r = a.win0 + (j - cnt) + a.ring_first;       // (ring_first is 0 unless the raw buffer is a ring)
-                r = r >= a.T_cap ? r - a.T_cap : r;
-                off = (seq_raw + r) * D;
-                kb = K; vb = V;
-            }
-            kr[u].load(kb + off + cl * EPL);
-            vr[u].load(vb + off + cl * EPL);
-        }
+    // One batch: U rows per lane group are loaded, scored against the NQ queries and folded into the running
+    // softmax.  pos[u] is the row's position for the causal test: its raw index, -1 for a summary (visible to every
+    // query), a huge value for a slot past the end.
+    auto fold = [&](const Raw<T, EPL> (&kr)[U], const Raw<T, EPL> (&vr)[U], const int (&pos)[U]) {
         float sc[NQ][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) d = fmaf(qv[i][e], kv[e], d);
                 d = group16_sum(d);
-                sc[i][u] = jrow[u] < lim[i] ? d : kNegBig;
+                sc[i][u] = pos[u] < lim[i] ? d : kNegBig;
             }
         }
         float alpha[NQ], p[NQ][U];
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
             l[i] *= alpha[i];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                p[i][u] = jrow[u] < lim[i] ? exp2f(sc[i][u] - m_new) : 0.f;
+                p[i][u] = pos[u] < lim[i] ? exp2f(sc[i][u] - m_new) : 0.f;
                 l[i] += p[i][u];
             }
             m[i] = m_new;
@@ -159,6 +161,43 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) o[i][e] = fmaf(p[i][u], vv[e], o[i][e]);
         }
+    };
+    constexpr int kPast = 0x3fffffff;
+
+    // ---- raw rows w0 .. w1-1 of the window (of the whole cache for the dense baseline) ----
+    for (int base = w0; base < w1; base += GROUPS * U) {
+        Raw<T, EPL> kr[U], vr[U];
+        int pos[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int w = base + grp + GROUPS * u;
+            pos[u] = w < w1 ? w : kPast;
+            int r = a.win0 + min(w, w1 - 1) + a.ring_first;       // (ring_first is 0 unless the raw buffer is a ring)
+            r = r >= a.T_cap ? r - a.T_cap : r;
+            const size_t off = (seq_raw + r) * D + cl * EPL;
+            kr[u].load(K + off);
+            vr[u].load(V + off);
+        }
+        fold(kr, vr, pos);
+    }
+    // ---- the kept summaries (first run only) ----
+    const int cnt = min(max(cnt_raw, 0), a.k_cap);
+    for (int base = 0; base < cnt; base += GROUPS * U) {
+        Raw<T, EPL> kr[U], vr[U];
+        int pos[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + grp + GROUPS * u;
+            pos[u] = j < cnt ? -1 : kPast;
+            const int jc = min(j, cnt - 1);
+            // (idx0[u] is entry min(j, k_cap - 1) of the list: the right one whenever row j exists)
+            int c = idx ? (base == 0 ? idx0[u] : idx[jc]) : jc;
+            c = min(max(c, 0), a.N_cap - 1);
+            const size_t off = (seq_sum + c) * D + cl * EPL;
+            kr[u].load(Kbar + off);
+            vr[u].load(Vbar + off);
+        }
+        fold(kr, vr, pos);
     }
 
     __shared__ float s_m[NQ][NW], s_l[NQ][NW], s_o[NQ][NW][D];
@@ -201,39 +240,58 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
                 Storage<T>::store(static_cast<T *>(a.O) + qrow[i] * D + tid, L > 0.f ? acc / L : 0.f);
             } else {
                 float *pp = a.part + (((size_t)s * R + (qg * NQ + i)) * a.nsplit + split) * (D + 2);
-                pp[tid] = acc;
-                if (tid == 0) { pp[D] = M; pp[D + 1] = L; }
+                store_device(pp + tid, acc);
+                if (tid == 0) { store_device(pp + D, M); store_device(pp + D + 1, L); }
             }
         }
     }
     if (a.nsplit == 1) return;
 
     // ---- the splits of these queries meet here: the last one to arrive merges them all ----
-    // Every thread makes its partial visible to the device before the workgroup draws its ticket; the
-    // workgroup that draws number nsplit - 1 knows that all partials are in memory, and reads them after a
-    // fence of its own.  The merge walks the splits in their own order, whoever arrived last.
+    // Partials and tickets travel with device-scope accesses (stores that write through the XCD's L2, loads that
+    // read past it), so no cache has to be written back or invalidated as a whole.  A workgroup waits until its
+    // partial stores are acknowledged, then draws its ticket; the workgroup that draws number nsplit - 1 therefore
+    // knows that all partials are in memory.  The merge walks the splits in their own order, whoever arrived last.
     __shared__ int s_last;
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // this thread's stores have completed
     __syncthreads();
     int32_t *ticket = a.tickets + ((size_t)s * qgroups + qg);
     if (tid == 0)
-        s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == a.nsplit - 1;
+        s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.nsplit - 1;
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
+    // the splits' maxima and sums first, one (query, split) per thread: a single round trip for all of them
+    __shared__ float s_pm[NQ][kMaxSplit], s_pl[NQ][kMaxSplit];
+    for (int e = tid; e < NQ * a.nsplit; e += 64 * NW) {
+        const int i = e / a.nsplit, sp = e - i * a.nsplit;
+        const int r = qg * NQ + i;
+        if (r < R) {
+            const float *ps = a.part + (((size_t)s * R + r) * a.nsplit + sp) * (D + 2);
+            s_pm[i][sp] = load_device(ps + D);
+            s_pl[i][sp] = load_device(ps + D + 1);
+        }
+    }
+    __syncthreads();
     const int t = tid % D;
     for (int i = tid / D; i < NQ; i += 64 * NW / D) {
         const int r = qg * NQ + i;
         if (r >= R) break;
-        const float *p = a.part + ((size_t)s * R + r) * a.nsplit * (D + 2);
+        const float *p = a.part + ((size_t)s * R + r) * a.nsplit * (D + 2) + t;
         float M = kNegBig;
-        for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, p[(size_t)sp * (D + 2) + D]);
+        for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, s_pm[i][sp]);
         float L = 0.f, acc = 0.f;
-        for (int sp = 0; sp < a.nsplit; ++sp) {
-            const float *ps = p + (size_t)sp * (D + 2);
-            const float f = exp2f(ps[D] - M);
-            L = fmaf(ps[D + 1], f, L);
-            acc = fmaf(ps[t], f, acc);
+        for (int sp0 = 0; sp0 < a.nsplit; sp0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = load_device(p + (size_t)min(sp0 + u, a.nsplit - 1) * (D + 2));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (sp0 + u < a.nsplit) {
+                    const float f = exp2f(s_pm[i][sp0 + u] - M);
+                    L = fmaf(s_pl[i][sp0 + u], f, L);
+                    acc = fmaf(v[u], f, acc);
+                }
+            }
         }
         Storage<T>::store(static_cast<T *>(a.O) + query_row(a, s, r) * D + t, L > 0.f ? acc / L : 0.f);
     }

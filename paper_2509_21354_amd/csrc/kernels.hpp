@@ -7,6 +7,8 @@
 
 namespace kvev {
 
+#define KVEV_ATTN_MAX_SPLIT 256   // decode attention: most splits of one query's rows
+
 struct AttnArgs {
     const void *Q, *K, *V, *Kbar, *Vbar;
     const int32_t *idx, *count;
@@ -49,6 +51,7 @@ struct LstmArgs {
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block
+    int fused;            // 1: the single-kernel form (d_g = 256, 32 sequences per workgroup, no projections in scratch)
 };
 
 // The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch is
@@ -90,5 +93,6 @@ hipError_t launch_pool_token_mfma(const PoolArgs &a, hipStream_t st);    // bf16
 size_t pool_token_mfma_lds(int d, int d_sum);                            // its LDS need in bytes
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
+hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

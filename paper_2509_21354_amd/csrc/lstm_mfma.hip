@@ -35,53 +35,13 @@
 // bf16 terms); the result is scaled back by 1/s, exactly.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "lstm_common.hpp"
 #include <utility>
 
 
 namespace kvev {
 
-typedef _Float16 f16_t;
-typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-
-// Gate nonlinearities through the hardware exp2 and reciprocal (about 1 ulp
-// each).  Their absolute error stays below ~2e-7 everywhere, which is what the
-// cell update needs (it consumes the values, not their logarithms): the
-// relative error of exp(x) grows like |x| * 2^-24, but it is multiplied by
-// s(1-s), which decays exponentially.
-__device__ __forceinline__ float sigmoid_hw(float x)
-{
-    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f));
-}
-__device__ __forceinline__ float tanh_hw(float x)
-{
-    return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * 2.8853900817779268f)), 1.0f);
-}
-
 constexpr int kTT = 8;   // steps per workgroup of the input projection (2 when that leaves compute units idle)
-
-// Hardware workgroup ids go round-robin over the 8 XCDs.  Give each XCD a
-// contiguous run of sequence groups, i.e. a few layers at a time, so that the
-// layer weights a workgroup streams every step stay in that XCD's 4 MB L2
-// instead of all layers cycling through all eight of them.
-__device__ __forceinline__ int xcd_order(int block, int nblocks)
-{
-    return nblocks % 8 == 0 ? (block % 8) * (nblocks / 8) + block / 8 : block;
-}
-
-// Geometry shared by the three kernels: unit tiles per wave, waves per workgroup,
-// and the order in which a wave walks its ITEMS = UT*KS weight items per step (an
-// item = the 4 gate fragments of one unit tile at one k-step, 4 KiB per wave): one
-// unit tile after the other, so that only 4 accumulators are live and the cell
-// update of a finished tile overlaps with the other waves' MFMAs.
-template <int DG> struct Geo {
-    static constexpr int UT = DG == 512 ? 4 : 2;   // keeps the workgroup at 8 waves (256 registers per lane)
-    static constexpr int NW = DG / (16 * UT);
-    static constexpr int KS = DG / 32;
-    static constexpr int THREADS = NW * 64;
-    static constexpr int ITEMS = UT * KS;
-    static constexpr int ut_of(int i) { return i / KS; }
-    static constexpr int ks_of(int i) { return i % KS; }
-};
 
 // Where the weight items of the recurrence live.  A CU pulls at most 64 bytes per
 // clock out of L2, which for d_g = 256 (512 KiB of W_hh per step) is longer than
@@ -210,20 +170,10 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs 
     }
 }
 
-// The power of two s that lifts max |W_hh| of a layer into [2^14, 2^15), from the
-// bit pattern of that maximum (s = 1 for an all-zero matrix).
-__device__ __forceinline__ int whh_scale_exp(uint32_t max_bits)
-{
-    const float m = __uint_as_float(max_bits);
-    int k = m > 0.f ? 14 - ilogbf(m) : 0;
-    return k > 100 ? 100 : k < -100 ? -100 : k;
-}
-
 // Weight preparation, one launch: blocks [0, nb_wih) re-lay W_ih in A-fragment order for the input projection
 // ([layer][wave][unit tile][gate][k-step][lane][8]); the kScaleBlocks blocks per layer after them each write the
 // largest finite |W_hh| of their share of the layer as a bit pattern (non-negative floats order like unsigned
 // integers) into a slot of their own: no atomics, nothing to clear between calls.
-constexpr int kScaleBlocks = 32;
 template <int DG, int D>
 __global__ __launch_bounds__(256) void lstm_prep_kernel(const bf16_t *W_ih, bf16x8_t *wih_packed, const bf16_t *W_hh,
                                                         uint32_t *max_bits, int L, int nb_wih)
@@ -268,15 +218,6 @@ __global__ __launch_bounds__(256) void lstm_prep_kernel(const bf16_t *W_ih, bf16
     if (t == 0) max_bits[b] = __float_as_uint(fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3])));
 }
 
-// max |W_hh| of a layer from the kScaleBlocks partial maxima
-__device__ __forceinline__ uint32_t whh_layer_max(const uint32_t *max_bits, int l)
-{
-    uint32_t m = 0;
-#pragma unroll 8
-    for (int p = 0; p < kScaleBlocks; ++p) m = max(m, max_bits[l * kScaleBlocks + p]);
-    return m;
-}
-
 // W_hh scaled, converted to fp16 and re-laid in A-fragment order so that every
 // wave-level load of the recurrence is one contiguous 1 KiB piece (the row-major
 // matrix would give 16 half-used cache lines per load):
@@ -310,6 +251,14 @@ template <int DG> __device__ void pack_whh_blocks(const LstmArgs &a, int block, 
         }
         packed[frag] = o;
     }
+}
+
+// The same re-layout as a launch of its own, for the single-kernel form of the gate (which has no input-projection
+// launch to ride in).
+template <int DG>
+__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_pack_whh_kernel(LstmArgs a)
+{
+    pack_whh_blocks<DG>(a, (int)blockIdx.x, (int)gridDim.x);
 }
 
 template <int DG>
@@ -935,6 +884,13 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
     }
     // W_hh fragments of the whole call: 16 bytes per thread and turn, about 4 turns per packing workgroup
     const size_t frags_h = (size_t)a.L * 4 * DG * DG / 8;
+    if constexpr (DG == 256) {
+        if (a.fused) {
+            const size_t want = (frags_h + (size_t)4 * Geo<DG>::THREADS - 1) / ((size_t)4 * Geo<DG>::THREADS);
+            hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)(want > 4096 ? 4096 : want)), dim3(Geo<DG>::THREADS), 0, st, a);
+            return launch_lstm_fused(a, st);
+        }
+    }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
         // few sequences: shorter runs of steps per workgroup so that the launch still covers the chip

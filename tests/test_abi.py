@@ -12,8 +12,8 @@ from paper_2509_21354_amd import synth
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "kvev.h")).read()
+def _declared(header="kvev.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(kvev_[a-z_0-9]+)\s*\(", text)))
 
@@ -21,8 +21,11 @@ def _declared():
 def test_library_exports_every_declared_symbol():
     names = _declared()
     assert set(kb.EXPORTS) == set(names)
+    hooks = _declared("kvev_test_hooks.h")
+    assert set(kb.TEST_HOOKS) == set(hooks)
+    assert not any("debug" in n for n in names)          # test hooks stay out of the public header
     L = kb.lib()
-    for n in names:
+    for n in names + hooks:
         assert getattr(L, n) is not None
     assert L.kvev_version() >= 100
     assert L.kvev_status_string(0) == b"ok"
@@ -36,6 +39,17 @@ def test_debug_pair_wait_validation():
     assert L.kvev_debug_pair_wait(16, -2, 0) == kb.ERR_INVALID_ARG
     assert L.kvev_debug_pair_wait(16, -1, 2) == kb.ERR_INVALID_ARG
     assert L.kvev_debug_pair_wait(1 << 22, -1, 0) == kb.OK      # the defaults
+    assert L.kvev_debug_lstm_fused_min_groups(-1) == kb.ERR_INVALID_ARG
+    big = kb.make_shape(synth.CONFIGS[3])
+    small = kb.make_shape(synth.CONFIGS[2])
+    w_small = kb.workspace_bytes(kb.OP_LSTM_GATE, small, 128)
+    assert L.kvev_debug_lstm_fused_min_groups(1) == kb.OK
+    try:       # the single-kernel form keeps no projections in scratch
+        assert 0 < kb.workspace_bytes(kb.OP_LSTM_GATE, small, 128) < w_small
+    finally:
+        assert L.kvev_debug_lstm_fused_min_groups(0) == kb.OK
+    assert kb.workspace_bytes(kb.OP_LSTM_GATE, small, 128) == w_small
+    assert kb.workspace_bytes(kb.OP_LSTM_GATE, big, 256) < (64 << 20)          # config 3: packed weights only
 
 
 FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first

@@ -251,6 +251,55 @@ def test_lstm_gate(cfg):
     assert (util[..., N:] == 9.0).all() and (gate[..., N:] == 9.0).all()
 
 
+FUSED_CASES = [
+    _cfg(181, "bf16", d=128, T=704, C=32, d_g=256, L=2, B=3, H=7),      # 21 sequences per layer: one ragged group of 32
+    _cfg(182, "bf16", d=64, T=832, C=32, d_g=256, L=1, B=5, H=16),      # 80 sequences: 2.5 groups, head width 64
+    _cfg(183, "bf16", d=128, T=64, C=32, d_g=256, L=3, B=2, H=16),      # two steps only: shorter than the summary ring
+    _cfg(184, "bf16", d=128, T=32, C=32, d_g=256, L=1, B=1, H=33),      # one step
+]
+
+
+@pytest.mark.parametrize("cfg", FUSED_CASES, ids=lambda c: c.name)
+def test_lstm_gate_single_kernel_form(cfg):
+    """The form of the gate that large launches take (d_g = 256: input projection and recurrence in one kernel, 32
+    sequences per workgroup), forced onto shapes the oracle finishes in seconds.  One call, then the same range cut
+    into calls that carry the state: bit-identical to the single call (the state is fp32 between steps)."""
+    N = cfg.T // cfg.C
+    N_cap = N + 2
+    w = synth.make_weights(cfg, "cpu")
+    Kbar, Vbar = _summaries(cfg, N_cap)
+    sh = kb.make_shape(cfg, N_cap=N_cap)
+    lead = (cfg.L, cfg.B, cfg.H)
+    gw = dev(w)
+    Kb, Vb = Kbar.cuda(), Vbar.cuda()
+    kb.kvev_debug_lstm_fused_min_groups(1)
+    try:
+        ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+        outs = []
+        for cuts in ([(0, N)], [(0, min(1, N)), (min(1, N), min(N, 5)), (min(N, 5), N)]):
+            h = torch.full(lead + (cfg.d_g,), 7.0, device="cuda")
+            c = torch.full_like(h, float("nan"))
+            util = torch.full(lead + (N_cap,), 9.0, device="cuda")
+            gate = torch.full_like(util, 9.0)
+            for a, b in cuts:
+                kb.kvev_lstm_gate(sh, Kb, Vb, kb.lstm_weights(gw), a, b, h, c, util, gate, ws)
+            torch.cuda.synchronize()
+            outs.append((h, c, util, gate))
+    finally:
+        kb.kvev_debug_lstm_fused_min_groups(0)
+    h, c, util, gate = outs[0]
+    rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
+    du = np.abs(util.cpu().numpy()[..., :N] - ru[..., :N]).max()
+    report(f"[{cfg.name}] single-kernel gate: max |util - oracle| = {du:.2e} over {N} steps")
+    assert du <= SCORE_TOL
+    assert np.abs(gate.cpu().numpy()[..., :N] - rg[..., :N]).max() <= SCORE_TOL
+    assert np.abs(h.cpu().numpy() - rh).max() <= SCORE_TOL
+    assert np.abs(c.cpu().numpy() - rc).max() <= 2 * SCORE_TOL
+    assert (util[..., N:] == 9.0).all() and (gate[..., N:] == 9.0).all()
+    for x, y in zip(outs[0], outs[1]):
+        assert torch.equal(x, y)
+
+
 def test_lstm_pair_wait_expires_cleanly():
     """The paired recurrence (d_g = 256, few groups) with one member's publications withheld and a tiny bound on
     the polls: both workgroups give up, every kernel ends normally, the launch's scores and cell state are NaN,
