@@ -89,6 +89,8 @@ def roof(name, kernel, cost, us, bound, workload=None):
 
 def rec_kernel_name(cfg):
     groups = cfg.L * ((cfg.B * cfg.kv_heads + 15) // 16)
+    if cfg.d_g == 256 and groups >= 257:
+        return f"lstm_fused_kernel<{cfg.d}>"
     paired = (cfg.d_g == 256 and groups <= 64) or (cfg.d_g == 512 and groups <= 128)
     return f"lstm_rec_pair_kernel<{cfg.d_g}>" if paired else f"lstm_rec_kernel<{cfg.d_g}>"
 
@@ -101,14 +103,21 @@ def recurrence_occupancy(cfg, gate_us):
     utilisation; profiles/mfma_counters.md has the counter-based figure)."""
     groups = cfg.L * ((cfg.B * cfg.kv_heads + 15) // 16)
     paired = rec_kernel_name(cfg).startswith("lstm_rec_pair")
-    cus = min(256, groups * (2 if paired else 1))
-    rounds = -(-groups * (2 if paired else 1) // 256)
-    mfma_per_group_step = 2 * (4 * cfg.d_g // 16) * (cfg.d_g // 32)
-    per_simd = mfma_per_group_step / (2 if paired else 1) / 4 * rounds
+    fused = rec_kernel_name(cfg).startswith("lstm_fused")
+    if fused:                      # 32 sequences per workgroup, the input projection's MFMAs inside the step
+        wgs = cfg.L * ((cfg.B * cfg.kv_heads + 31) // 32)
+        cus, rounds = min(256, wgs), -(-wgs // 256)
+        mfma_per_group_step = 2 * (2 * (4 * cfg.d_g // 16) * (cfg.d_g // 32) + (4 * cfg.d_g // 16) * (2 * cfg.d // 32))
+        per_simd = mfma_per_group_step / 4 * rounds
+    else:
+        cus = min(256, groups * (2 if paired else 1))
+        rounds = -(-groups * (2 if paired else 1) // 256)
+        mfma_per_group_step = 2 * (4 * cfg.d_g // 16) * (cfg.d_g // 32)
+        per_simd = mfma_per_group_step / (2 if paired else 1) / 4 * rounds
     us_step = gate_us / cfg.N
     busy_us = per_simd * 16 / 2400.0
     return {"dependent_steps": cfg.N, "us_per_step": round(us_step, 3), "compute_units_occupied": cus,
-            "workgroups_per_sequence_group": 2 if paired else 1,
+            "workgroups_per_sequence_group": 2 if paired else 1, "sequences_per_workgroup": 32 if fused else 16,
             "mfma_pipe_us_per_step_per_simd": round(busy_us, 3), "mfma_pipe_busy_frac_of_occupied_simds": round(busy_us / us_step, 3)}
 
 
@@ -142,7 +151,10 @@ class Bench:
 
         def pool(t): kb.kvev_chunk_pool(sh, t["K"], t["V"], kb.POOL_MLP, wK, wV, 0, N, st.Kbar, st.Vbar, st.ws)
 
-        def gate(t): kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, lw, 0, N, st.h, st.c, st.util, st.gate, st.ws)
+        # the gate's weights are static across decode steps: packed once, outside the timed region
+        kb.kvev_lstm_prepare(sh, lw, st.packed)
+
+        def gate(t): kb.kvev_lstm_gate_prepared(sh, st.Kbar, st.Vbar, lw, st.packed, 0, N, st.h, st.c, st.util, st.gate, st.ws)
 
         def select(t): kb.kvev_select(sh, st.util, st.gate, kb.SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)
 
@@ -157,9 +169,9 @@ class Bench:
         self.mfma = mfma
         self.kernels = {
             "pool": "pool_mfma_kernel" if mfma and cfg.d_sum % 32 == 0 else "pool_generic_kernel",
-            # one kvev_lstm_gate call = the recurrence launches of its scratch blocks (the input projection is computed
-            # inside them); the HIP events bracket the call
-            "gate": (f"{rec_kernel_name(cfg)} (the whole kvev_lstm_gate call)"
+            # one kvev_lstm_gate_prepared call (weights packed once, before the timed region) = per scratch block an input
+            # projection and a recurrence launch, or the single fused kernel; the HIP events bracket the call
+            "gate": (f"{rec_kernel_name(cfg)} (the whole kvev_lstm_gate_prepared call)"
                      if mfma and cfg.d_g in (64, 128, 256, 512) else "lstm_generic_kernel"),
             "select": "select_kernel",
             "attend": "attn_mq_kernel" if mfma and Tq * (cfg.H // cfg.kv_heads) >= 16 else "attn_decode_kernel",
@@ -455,12 +467,13 @@ def streaming_cfg4(torch, kb, synth):
     O4 = torch.empty_like(kv4["Q"])
     wK4, wV4, lw4 = kb.mlp_weights(w4, "K"), kb.mlp_weights(w4, "V"), kb.lstm_weights(w4)
     sh4 = s4.shape
+    kb.kvev_lstm_prepare(sh4, lw4, s4.packed)          # static weights: packed once
 
     def frame(si, done):
         sh4.T = (si + 1) * c4.frame
         n4 = sh4.T // c4.C
         kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
-        kb.kvev_lstm_gate(sh4, s4.Kbar, s4.Vbar, lw4, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
+        kb.kvev_lstm_gate_prepared(sh4, s4.Kbar, s4.Vbar, lw4, s4.packed, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
         kb.kvev_select(sh4, s4.util, s4.gate, kb.SELECT_TOPK, c4.k, 0.0, s4.k_cap, s4.idx, s4.count)
         for j in range(c4.decode_per_step):
             kb.kvev_gated_attention(sh4, q4[si, j], 1, kv4["K"], kv4["V"], s4.Kbar, s4.Vbar, s4.idx, s4.count,
@@ -506,7 +519,7 @@ def streaming_cfg4(torch, kb, synth):
         Kr4[..., r0:r0 + c4.frame, :] = kv4["K"][..., T4 - c4.frame:T4, :]     # stands for the model's cache write
         Vr4[..., r0:r0 + c4.frame, :] = kv4["V"][..., T4 - c4.frame:T4, :]
         kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
-        kb.kvev_lstm_gate(sh4, s4.Kbar, s4.Vbar, lw4, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
+        kb.kvev_lstm_gate_prepared(sh4, s4.Kbar, s4.Vbar, lw4, s4.packed, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
         ncand = max(0, T4 - c4.W) // c4.C
         if ncand > ncand_old:
             kb.kvev_retain(sh4, c4.k, kc4, kb.RowsFrom(s4.Kbar, ncand_old, c4.d), kb.RowsFrom(s4.Vbar, ncand_old, c4.d),

@@ -42,7 +42,8 @@ enum { KVEV_F32 = 0, KVEV_BF16 = 1 };           /* storage type of Q/K/V, summar
 enum { KVEV_POOL_MEAN = 0, KVEV_POOL_MLP = 1, KVEV_POOL_MAX = 2, KVEV_POOL_TOKEN_MLP = 3 };
 enum { KVEV_SELECT_TOPK = 0, KVEV_SELECT_THRESHOLD = 1 };
 enum { KVEV_OP_CHUNK_POOL = 0, KVEV_OP_LSTM_GATE = 1, KVEV_OP_SELECT = 2,
-       KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4, KVEV_OP_COMPACT_ATTENTION = 5 };
+       KVEV_OP_GATED_ATTENTION = 3, KVEV_OP_DENSE_ATTENTION = 4, KVEV_OP_COMPACT_ATTENTION = 5,
+       KVEV_OP_LSTM_PREPARE = 6, KVEV_OP_LSTM_GATE_PREPARED = 7 };
 
 /* Problem shape.  L layers are batched in one call; a "sequence" is one
  * (layer, batch row, head) triple, S = L*B*H of them, each independent.
@@ -108,19 +109,52 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  *               pass them back unchanged to continue the stream
  *               (chunk_begin > 0)
  *   util, gate  [L,B,H,N_cap] fp32, entries [chunk_begin, chunk_end) written
- * Needs 0 <= chunk_begin <= chunk_end <= N_cap.  Workspace: see
- * kvev_workspace_bytes (fp32 input projections of a block of steps); any size
- * from one step's worth up is accepted, smaller blocks mean more launches.
- * Calls that share a workspace must not overlap (it also carries what the
- * workgroups of one launch exchange).  Small launches (bf16; d_g = 256 with at
- * most 64 groups of 16 sequences, d_g = 512 with at most 128) run each group on two cooperating
- * workgroups, which wait for each other's data with a bounded number of polls;
- * should the bound ever expire (the GPU held by other work for seconds), the
- * launch ends normally and its util, gate and c entries are NaN.
+ * Needs 0 <= chunk_begin <= chunk_end <= N_cap; h and c 16-byte aligned.
+ * Workspace: see kvev_workspace_bytes: a 256-byte head, the weights re-laid for
+ * the matrix cores (written by every call; kvev_lstm_gate_prepared takes them
+ * from the caller instead), and for most shapes fp32 input projections of a
+ * block of steps: any size from one step's worth up is accepted, smaller blocks
+ * mean more launches.  Launches of bf16 storage with d_g = 256 that give every
+ * compute unit a group of 32 sequences run as one kernel and keep no
+ * projections at all.  Calls that share a workspace must not overlap (it also
+ * carries what the workgroups of one launch exchange).
+ * Status word: the first int32 of the workspace.  Small launches (bf16; d_g =
+ * 256 with at most one group of 16 sequences per 4 compute units of the device,
+ * d_g = 512 per 2) run each group on two cooperating workgroups, which wait for
+ * each other's data with a bounded number of polls.  Should the bound ever
+ * expire (the GPU held by other work for seconds), the launch still ends
+ * normally, its util, gate and c entries are NaN, and it stores 1 in the status
+ * word.  The library never clears the word: fill the workspace with zeros
+ * before its first use and read the word whenever you synchronise; non-zero
+ * means that the scores of some call since then are not to be used.
  * Errors: INVALID_ARG, UNSUPPORTED as above; WORKSPACE if ws is too small. */
 int kvev_lstm_gate(const kvev_shape *shape, const void *Kbar, const void *Vbar,
                    const kvev_lstm_w *w, int chunk_begin, int chunk_end, float *h, float *c,
                    float *util, float *gate, void *ws, size_t ws_bytes, void *stream);
+
+/* The weights of Eq. 3 in the form the matrix-core kernels of the gate read:
+ * W_ih and W_hh in fragment order, W_hh scaled by a per-layer power of two and
+ * converted so that its products with the two-term state are exact.  The
+ * result depends on the weights alone, so a caller whose weights do not change
+ * between decode steps prepares them once and passes `packed` to every
+ * kvev_lstm_gate_prepared call, which then skips this work (two launches per
+ * call).  `packed` is caller-owned device memory of at least
+ * kvev_workspace_bytes(KVEV_OP_LSTM_PREPARE, shape, 0, 0) bytes (0 for shapes
+ * the matrix-core kernels do not take: then the call does nothing and `packed`
+ * may be NULL), 16-byte aligned; only L, d, d_g and dtype of `shape` are used
+ * beyond validation.  Errors: INVALID_ARG, UNSUPPORTED as kvev_lstm_gate;
+ * WORKSPACE for a missing, misaligned or short `packed`. */
+int kvev_lstm_prepare(const kvev_shape *shape, const kvev_lstm_w *w, void *packed, size_t packed_bytes,
+                      void *stream);
+
+/* kvev_lstm_gate (Eq. 3) with weights prepared by kvev_lstm_prepare for the
+ * same shape and `w`: same results bit for bit.  `w` is still read (biases and
+ * the utility head).  Workspace: kvev_workspace_bytes(KVEV_OP_LSTM_GATE_PREPARED,
+ * ...), which lacks the packed weights; status word as kvev_lstm_gate. */
+int kvev_lstm_gate_prepared(const kvev_shape *shape, const void *Kbar, const void *Vbar,
+                            const kvev_lstm_w *w, const void *packed, size_t packed_bytes,
+                            int chunk_begin, int chunk_end, float *h, float *c, float *util, float *gate,
+                            void *ws, size_t ws_bytes, void *stream);
 
 /* Retention.  Candidates are chunks 0 .. N_cand-1.
  * KVEV_SELECT_TOPK: keep the min(k, N_cand) candidates of largest util, ties
@@ -223,7 +257,8 @@ int kvev_compact_attention(const kvev_shape *shape, const void *Q, int Tq, const
                            int win_first, const void *Kc, const void *Vc, const int32_t *count, int k_cap,
                            int causal, void *O, void *ws, size_t ws_bytes, void *stream);
 
-/* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape.  `n` is Tq
+/* Scratch bytes that `op` (a KVEV_OP_* value) wants for this shape
+ * (KVEV_OP_LSTM_PREPARE: the size of the packed weights).  `n` is Tq
  * for the attention ops and chunk_end - chunk_begin for pool / gate; k_cap is
  * used by KVEV_OP_GATED_ATTENTION and KVEV_OP_COMPACT_ATTENTION only.  Returns 0 when none is needed or the
  * arguments are invalid. */

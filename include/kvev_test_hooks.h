@@ -11,18 +11,15 @@
 extern "C" {
 #endif
 
-/* For tests of the gate's failure path.  Small launches
- * of kvev_lstm_gate run a group of sequences on two workgroups that wait for
- * each other's data (see there).  This sets, for later calls in this process,
- * the number of polls one such wait may take (default 1 << 22) and the member
- * (0 or 1; -1 = none, the default) that withholds what it would publish, so
- * that its partner's wait expires: every kernel still ends normally and the
- * affected launch's util, gate and c come back NaN.  write_through = 1 makes
- * the two workgroups publish with device-scope (write-through) stores even
- * when they share an L2 and plain stores would do: the path taken when they
- * do not.  Results are the same bits either way.   Errors: INVALID_ARG for spin_limit < 1, a member outside -1..1 or
- * write_through outside 0..1. */
-int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through);
+/* For tests of the gate's failure path.  Small launches of kvev_lstm_gate run a
+ * group of sequences on two workgroups that wait for each other's data (see
+ * kvev.h).  This sets, for later calls in this process, the number of polls one
+ * such wait may take (default 1 << 22) and the member (0 or 1; -1 = none, the
+ * default) that withholds what it would publish, so that its partner's wait
+ * expires: every kernel still ends normally, the affected launch's util, gate
+ * and c come back NaN and the status word of its workspace is set.
+ * Errors: INVALID_ARG for spin_limit < 1 or a member outside -1..1. */
+int kvev_debug_pair_wait(int spin_limit, int mute_member);
 
 /* For parity tests of the single-kernel form of the gate (bf16, d_g = 256), which the
  * library takes for launches of at least `min_groups` groups of 16 sequences

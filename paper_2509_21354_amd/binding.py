@@ -24,8 +24,9 @@ F32, BF16 = 0, 1
 POOL_MEAN, POOL_MLP, POOL_MAX, POOL_TOKEN_MLP = 0, 1, 2, 3
 SELECT_TOPK, SELECT_THRESHOLD = 0, 1
 OP_CHUNK_POOL, OP_LSTM_GATE, OP_SELECT, OP_GATED_ATTENTION, OP_DENSE_ATTENTION, OP_COMPACT_ATTENTION = range(6)
+OP_LSTM_PREPARE, OP_LSTM_GATE_PREPARED = 6, 7
 
-EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
+EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_lstm_prepare", "kvev_lstm_gate_prepared", "kvev_select", "kvev_gated_attention",
            "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
            "kvev_status_string", "kvev_last_hip_error", "kvev_version")
 TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups")      # include/kvev_test_hooks.h
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_chunk_pool.argtypes = [shp, vp, vp, ci, ctypes.POINTER(MlpW), ctypes.POINTER(MlpW), ci, ci,
                                       vp, vp, vp, sz, vp]
         L.kvev_lstm_gate.argtypes = [shp, vp, vp, ctypes.POINTER(LstmW), ci, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.kvev_lstm_prepare.argtypes = [shp, ctypes.POINTER(LstmW), vp, sz, vp]
+        L.kvev_lstm_gate_prepared.argtypes = [shp, vp, vp, ctypes.POINTER(LstmW), vp, sz, ci, ci, vp, vp, vp, vp, vp, sz, vp]
         L.kvev_select.argtypes = [shp, vp, vp, ci, ci, ctypes.c_float, ci, vp, vp, vp]
         L.kvev_gated_attention.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_gated_attention_static.argtypes = [shp, vp, ci, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp]
@@ -75,14 +78,14 @@ def lib() -> ctypes.CDLL:
         L.kvev_compact_attention.argtypes = [shp, vp, ci, vp, vp, ci, vp, vp, vp, ci, ci, vp, vp, sz, vp]
         L.kvev_workspace_bytes.argtypes = [ci, shp, ci, ci]
         L.kvev_workspace_bytes.restype = sz
-        L.kvev_debug_pair_wait.argtypes = [ci, ci, ci]
+        L.kvev_debug_pair_wait.argtypes = [ci, ci]
         L.kvev_debug_pair_wait.restype = ci
         L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
         L.kvev_debug_lstm_fused_min_groups.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
-        for n in ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_select", "kvev_gated_attention",
+        for n in ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_lstm_prepare", "kvev_lstm_gate_prepared", "kvev_select", "kvev_gated_attention",
                   "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_version"):
             getattr(L, n).restype = ci
         _lib = L
@@ -131,8 +134,8 @@ def make_shape(cfg=None, **kw) -> Shape:
     return Shape(**v)
 
 
-def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1, write_through: int = 0) -> None:
-    _check(lib().kvev_debug_pair_wait(spin_limit, mute_member, write_through), "kvev_debug_pair_wait")
+def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> None:
+    _check(lib().kvev_debug_pair_wait(spin_limit, mute_member), "kvev_debug_pair_wait")
 
 
 def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:
@@ -167,6 +170,22 @@ def kvev_lstm_gate(shape: Shape, Kbar, Vbar, w, chunk_begin, chunk_end, h, c, ut
                               chunk_end, _ptr(h), _ptr(c), _ptr(util), _ptr(gate), _ptr(ws),
                               ws.numel() if ws is not None else 0, _stream())
     _check(st, "kvev_lstm_gate")
+
+
+def kvev_lstm_prepare(shape: Shape, w, packed):
+    lw = LstmW(*[t.data_ptr() for t in w])
+    st = lib().kvev_lstm_prepare(ctypes.byref(shape), ctypes.byref(lw), _ptr(packed),
+                                 packed.numel() if packed is not None else 0, _stream())
+    _check(st, "kvev_lstm_prepare")
+
+
+def kvev_lstm_gate_prepared(shape: Shape, Kbar, Vbar, w, packed, chunk_begin, chunk_end, h, c, util, gate, ws=None):
+    lw = LstmW(*[t.data_ptr() for t in w])
+    st = lib().kvev_lstm_gate_prepared(ctypes.byref(shape), _ptr(Kbar), _ptr(Vbar), ctypes.byref(lw), _ptr(packed),
+                                       packed.numel() if packed is not None else 0, chunk_begin, chunk_end, _ptr(h),
+                                       _ptr(c), _ptr(util), _ptr(gate), _ptr(ws), ws.numel() if ws is not None else 0,
+                                       _stream())
+    _check(st, "kvev_lstm_gate_prepared")
 
 
 def kvev_select(shape: Shape, util, gate, mode, k, tau, k_cap, idx, count):
@@ -235,6 +254,7 @@ class DecodeState:
         # the gate's scratch, and the attention calls' own (their tickets must stay zero between calls, so it is
         # never lent to the gate)
         self.ws = alloc_workspace(workspace_bytes(OP_LSTM_GATE, full, self.N_cap), dev)
+        self.packed = alloc_workspace(workspace_bytes(OP_LSTM_PREPARE, full, 0), dev)    # for kvev_lstm_prepare
         nbytes = max(workspace_bytes(OP_GATED_ATTENTION, full, Tq, self.k_cap),
                      workspace_bytes(OP_DENSE_ATTENTION, full, Tq),
                      max(workspace_bytes(OP_GATED_ATTENTION, make_shape(cfg, T=t, T_cap=T_cap, N_cap=self.N_cap),

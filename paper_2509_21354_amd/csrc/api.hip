@@ -200,7 +200,25 @@ static bool lstm_takes_mfma(const kvev_shape *sh)
 
 // Bound on the polls of one wait of the paired recurrence (each poll is a round trip to memory, about a
 // microsecond: seconds in all), and the member whose publications are withheld; kvev_debug_pair_wait changes them.
-static std::atomic<int> g_pair_spin_limit{1 << 22}, g_pair_mute{-1}, g_pair_write_through{0};
+static std::atomic<int> g_pair_spin_limit{1 << 22}, g_pair_mute{-1};
+
+// Compute units of the current device (what decides whether the workgroups of a paired launch can all be resident);
+// 256 when no device answers (argument checks and scratch queries also run on machines without a GPU).
+static int device_compute_units()
+{
+    static std::atomic<int> cached{0};
+    int n = cached.load();
+    if (n > 0) return n;
+    int dev = 0, v = 0;
+    n = 256;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        n = v;
+    else
+        (void)hipGetLastError();         // not an error of any launch of ours
+    cached.store(n);
+    return n;
+}
 
 static long long lstm_groups(const kvev_shape *sh)
 {
@@ -224,10 +242,16 @@ static size_t lstm_ws_weights(const kvev_shape *sh)
     return (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2 + ((size_t)sh->L * 32 * 4 + 255) / 256 * 256;
 }
 
-// ... followed by the exchange slots of the paired recurrence, where it applies.
-static size_t lstm_ws_pack(const kvev_shape *sh)
+// The gate's scratch: a 256-byte head (its first word is the status word), the packed weights unless the caller
+// keeps them (kvev_lstm_prepare), the exchange slots of the paired recurrence where it applies, then the projections.
+constexpr size_t kLstmWsHead = 256;
+static size_t lstm_exch_bytes(const kvev_shape *sh)
 {
-    return lstm_takes_mfma(sh) ? lstm_ws_weights(sh) + lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh)) : 0;
+    return lstm_takes_fused(sh) ? 0 : lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh), device_compute_units());
+}
+static size_t lstm_ws_pack(const kvev_shape *sh, bool prepared)
+{
+    return lstm_takes_mfma(sh) ? kLstmWsHead + (prepared ? 0 : lstm_ws_weights(sh)) + lstm_exch_bytes(sh) : 0;
 }
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
@@ -285,20 +309,40 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 
-int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, const kvev_lstm_w *w,
-                   int chunk_begin, int chunk_end, float *h, float *c, float *util, float *gate, void *ws,
-                   size_t ws_bytes, void *stream)
+static int lstm_check_weights(const kvev_lstm_w *w)
 {
-    int rc = check_shape(sh);
-    if (rc) return rc;
-    if (!Kbar || !Vbar || !w || !h || !c || !util || !gate || !aligned16(Kbar) || !aligned16(Vbar))
-        return KVEV_ERR_INVALID_ARG;
+    if (!w) return KVEV_ERR_INVALID_ARG;
     const void *ptrs[6] = {w->W_ih, w->W_hh, w->b_ih, w->b_hh, w->w_s, w->b_s};
     for (int i = 0; i < 6; ++i)
         if (!ptrs[i] || (i < 5 && !aligned16(ptrs[i]))) return KVEV_ERR_INVALID_ARG;
+    return KVEV_OK;
+}
+
+// where the packed weights sit inside a buffer that begins at `base`
+static void lstm_packed_pointers(const kvev_shape *sh, void *base, LstmArgs &a)
+{
+    a.whh_packed = static_cast<const bf16x8_t *>(base);
+    a.wih_packed = a.whh_packed + (size_t)sh->L * 4 * sh->d_g * sh->d_g / 8;
+    a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(base) +
+                                            (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
+}
+
+static int lstm_gate_common(const kvev_shape *sh, const void *Kbar, const void *Vbar, const kvev_lstm_w *w,
+                            const void *packed, size_t packed_bytes, bool prepared, int chunk_begin, int chunk_end,
+                            float *h, float *c, float *util, float *gate, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    if (!Kbar || !Vbar || !h || !c || !util || !gate || !aligned16(Kbar) || !aligned16(Vbar) || !aligned16(h) ||
+        !aligned16(c))
+        return KVEV_ERR_INVALID_ARG;
+    rc = lstm_check_weights(w);
+    if (rc) return rc;
     if (chunk_begin < 0 || chunk_begin > chunk_end || chunk_end > sh->N_cap) return KVEV_ERR_INVALID_ARG;
     if (sizeof(float) * (2 * (size_t)sh->d + 6 * (size_t)sh->d_g) > 64 * 1024 && !lstm_takes_mfma(sh))
         return KVEV_ERR_UNSUPPORTED;
+    if (prepared && lstm_takes_mfma(sh) && (!packed || !aligned16(packed) || packed_bytes < lstm_ws_weights(sh)))
+        return KVEV_ERR_WORKSPACE;
     if (chunk_begin == chunk_end) return KVEV_OK;
 
     LstmArgs a;
@@ -311,27 +355,65 @@ int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, con
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (lstm_takes_mfma(sh)) {
-        const size_t per = lstm_ws_per_step(sh), pack = lstm_ws_pack(sh);
+        const size_t per = lstm_ws_per_step(sh), pack = lstm_ws_pack(sh, prepared);
         if (!ws || !aligned16(ws) || ws_bytes < pack + per) return KVEV_ERR_WORKSPACE;
         a.fused = lstm_takes_fused(sh) ? 1 : 0;
         size_t tb = a.fused ? (size_t)(chunk_end - chunk_begin) : (ws_bytes - pack) / per;
         if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
         a.tb = (int)tb;
-        a.whh_packed = static_cast<const bf16x8_t *>(ws);
-        a.wih_packed = a.whh_packed + (size_t)sh->L * 4 * sh->d_g * sh->d_g / 8;
-        a.whh_max_bits = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(ws) +
-                                                (size_t)sh->L * 4 * sh->d_g * ((size_t)sh->d_g + 2 * sh->d) * 2);
-        a.exch_bytes = lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh));
+        unsigned char *p = static_cast<unsigned char *>(ws);
+        a.status = reinterpret_cast<int32_t *>(p);
+        p += kLstmWsHead;
+        a.prepared = prepared ? 1 : 0;
+        if (prepared) {
+            lstm_packed_pointers(sh, const_cast<void *>(packed), a);
+        } else {
+            lstm_packed_pointers(sh, p, a);
+            p += lstm_ws_weights(sh);
+        }
+        a.exch_bytes = lstm_exch_bytes(sh);
+        a.exch = a.exch_bytes ? p : nullptr;
+        a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         a.pair_spin_limit = g_pair_spin_limit.load();
         a.pair_mute = g_pair_mute.load();
-        a.pair_write_through = g_pair_write_through.load();
-        a.exch = a.exch_bytes ? static_cast<unsigned char *>(ws) + lstm_ws_weights(sh) : nullptr;
-        a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         e = launch_lstm_mfma(a, st);
     } else {
         e = launch_lstm_generic(a, sh->dtype, st);
     }
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_lstm_gate(const kvev_shape *sh, const void *Kbar, const void *Vbar, const kvev_lstm_w *w,
+                   int chunk_begin, int chunk_end, float *h, float *c, float *util, float *gate, void *ws,
+                   size_t ws_bytes, void *stream)
+{
+    return lstm_gate_common(sh, Kbar, Vbar, w, nullptr, 0, false, chunk_begin, chunk_end, h, c, util, gate, ws, ws_bytes,
+                            stream);
+}
+
+int kvev_lstm_prepare(const kvev_shape *sh, const kvev_lstm_w *w, void *packed, size_t packed_bytes, void *stream)
+{
+    int rc = check_shape(sh);
+    if (rc) return rc;
+    rc = lstm_check_weights(w);
+    if (rc) return rc;
+    if (!lstm_takes_mfma(sh)) return KVEV_OK;          // the generic kernels read the weights as they are
+    if (!packed || !aligned16(packed) || packed_bytes < lstm_ws_weights(sh)) return KVEV_ERR_WORKSPACE;
+    LstmArgs a;
+    memset(&a, 0, sizeof a);
+    a.W_ih = w->W_ih; a.W_hh = w->W_hh;
+    a.L = sh->L; a.d = sh->d; a.d_g = sh->d_g;
+    lstm_packed_pointers(sh, packed, a);
+    hipError_t e = launch_lstm_prepare(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
+int kvev_lstm_gate_prepared(const kvev_shape *sh, const void *Kbar, const void *Vbar, const kvev_lstm_w *w,
+                            const void *packed, size_t packed_bytes, int chunk_begin, int chunk_end, float *h, float *c,
+                            float *util, float *gate, void *ws, size_t ws_bytes, void *stream)
+{
+    return lstm_gate_common(sh, Kbar, Vbar, w, packed, packed_bytes, true, chunk_begin, chunk_end, h, c, util, gate, ws,
+                            ws_bytes, stream);
 }
 
 int kvev_select(const kvev_shape *sh, const float *util, const float *gate, int mode, int k, float tau,
@@ -407,13 +489,11 @@ int kvev_retain(const kvev_shape *sh, int k, int k_cap, const void *Kbar_new, co
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 
-int kvev_debug_pair_wait(int spin_limit, int mute_member, int write_through)
+int kvev_debug_pair_wait(int spin_limit, int mute_member)
 {
-    if (spin_limit < 1 || mute_member < -1 || mute_member > 1 || write_through < 0 || write_through > 1)
-        return KVEV_ERR_INVALID_ARG;
+    if (spin_limit < 1 || mute_member < -1 || mute_member > 1) return KVEV_ERR_INVALID_ARG;
     g_pair_spin_limit = spin_limit;
     g_pair_mute = mute_member;
-    g_pair_write_through = write_through;
     return KVEV_OK;
 }
 
@@ -428,12 +508,15 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
 {
     if (check_shape(sh, op != KVEV_OP_COMPACT_ATTENTION) != KVEV_OK || n < 0) return 0;
     switch (op) {
-    case KVEV_OP_LSTM_GATE: {
+    case KVEV_OP_LSTM_GATE:
+    case KVEV_OP_LSTM_GATE_PREPARED: {
         const size_t per = lstm_ws_per_step(sh);
         const int tb = n < 128 ? n : 128;
         if (!lstm_takes_mfma(sh)) return 0;
-        return lstm_ws_pack(sh) + per * (size_t)(tb < 1 ? 1 : tb);
+        return lstm_ws_pack(sh, op == KVEV_OP_LSTM_GATE_PREPARED) + per * (size_t)(tb < 1 ? 1 : tb);
     }
+    case KVEV_OP_LSTM_PREPARE:
+        return lstm_takes_mfma(sh) ? lstm_ws_weights(sh) : 0;
     case KVEV_OP_GATED_ATTENTION: {
         if (k_cap < 0) return 0;
         const int ncand = n_cand_of(sh);

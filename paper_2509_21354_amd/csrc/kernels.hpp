@@ -47,22 +47,23 @@ struct LstmArgs {
     size_t exch_bytes;    // 0: one workgroup per sequence group
     int pair_spin_limit;  // polls a wave of the paired recurrence spends on one wait before it gives up
     int pair_mute;        // member (0, 1) whose publications are withheld, -1: none (failure-path tests only)
-    int pair_write_through;   // 1: publish with device-scope stores even behind a shared L2 (tests of that path)
+    int32_t *status;      // workspace: word that a launch sets to 1 when a bounded wait expired (never cleared by the library)
+    int prepared;         // 1: the packed weights are already in place (kvev_lstm_prepare), 0: this call packs them first
     int L, BH, d, N_cap, d_g;
     int c0, c1;
     int tb;               // steps per workspace block
     int fused;            // 1: the single-kernel form (d_g = 256, 32 sequences per workgroup, no projections in scratch)
 };
 
-// The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch is
-// small enough for all of them to be resident together (bounded waits in the kernel cover the rest): up to 64 groups
-// at d_g = 256, up to 128 (one workgroup per compute unit) at d_g = 512, where a single workgroup is bound by
-// the weight stream out of L2 and a pair halves it.  The exchange needs 64 KiB of scratch per group and 256
+// The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch has at most
+// one workgroup per two compute units at d_g = 256, per compute unit at d_g = 512 (where a single workgroup is bound
+// by the weight stream out of L2 and a pair halves it): then all of them can be resident together on an idle
+// device (bounded waits in the kernel cover the rest).  The exchange needs 64 KiB of scratch per group and 256
 // hidden units.  0: not paired.
-inline size_t lstm_pair_exch_bytes(int d_g, long long groups)
+inline size_t lstm_pair_exch_bytes(int d_g, long long groups, int compute_units)
 {
-    if (d_g == 256 && groups <= 64) return (size_t)groups * 65536;
-    if (d_g == 512 && groups <= 128) return (size_t)groups * 131072;
+    if (d_g == 256 && 4 * groups <= compute_units) return (size_t)groups * 65536;
+    if (d_g == 512 && 2 * groups <= compute_units) return (size_t)groups * 131072;
     return 0;
 }
 
@@ -93,6 +94,7 @@ hipError_t launch_pool_token_mfma(const PoolArgs &a, hipStream_t st);    // bf16
 size_t pool_token_mfma_lds(int d, int d_sum);                            // its LDS need in bytes
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
+hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st);       // bf16: the packed weights alone
 hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

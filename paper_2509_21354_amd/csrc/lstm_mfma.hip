@@ -36,6 +36,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "lstm_common.hpp"
+#include <atomic>
 #include <utility>
 
 
@@ -94,20 +95,14 @@ __device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, 
 // sequence and step), written as 1 KiB per wave-level store in the fragment layout the recurrence reads back.
 template <int DG> __device__ void pack_whh_blocks(const LstmArgs &a, int block, int nblocks);
 
-// (ny_proj rows of the grid project; the rows after them, present in a call's first launch only, re-lay W_hh
-// for the recurrence that follows: both only need what the preparation kernel left, so they share a launch)
 template <int DG, int D, int TT>
-__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb, int ny_proj)
+__global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_inproj_kernel(LstmArgs a, int t0, int nb)
 {
     constexpr int KS = 2 * D / 32, UT = Geo<DG>::UT, XP = 2 * D + 8, THREADS = Geo<DG>::THREADS;
     if (a.exch_bytes) {      // the paired recurrence that follows starts from cleared exchange slots
         const size_t nthreads = (size_t)gridDim.x * gridDim.y * THREADS;
         for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * THREADS + threadIdx.x; i * 16 < a.exch_bytes; i += nthreads)
             reinterpret_cast<uint4 *>(a.exch)[i] = make_uint4(0u, 0u, 0u, 0u);
-    }
-    if ((int)blockIdx.y >= ny_proj) {
-        pack_whh_blocks<DG>(a, ((int)blockIdx.y - ny_proj) * gridDim.x + blockIdx.x, ((int)gridDim.y - ny_proj) * gridDim.x);
-        return;
     }
     extern __shared__ __align__(16) unsigned char smem_in[];
     bf16_t *s_x = reinterpret_cast<bf16_t *>(smem_in);           // [TT][16][XP]
@@ -481,10 +476,11 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 // per step against 20 us.
 //
 // Every wait is bounded: a wave that does not see its partner's data within a.pair_spin_limit polls raises a flag in
-// LDS, the workgroup leaves the step loop together after the next barrier and marks the launch's scores as NaN.
+// LDS, the workgroup leaves the step loop together after the next barrier, marks the launch's scores as NaN and sets
+// the status word at the head of the caller's scratch (it stays set until the caller clears it).
 // Members of a pair are neighbours in the launch order; workgroups are started in that order here, so a launch that
-// does not fit the chip at once still completes pair by pair (the bound covers any other case).  It is used up to
-// one workgroup per CU.
+// does not fit the chip at once still completes pair by pair (the bound covers any other case).  The host takes this
+// kernel only while the launch has at most one workgroup per compute unit of the device.
 // Geometry of the paired kernel: 8 waves, each with UT unit tiles of the workgroup's half of the hidden units; a
 // weight item is the 4 gate fragments of one tile at one k-step (4 KiB per wave), walked k-step by k-step (the B
 // operand of a k-step serves all tiles), own half of the k range first.  d_g = 256 keeps all 8 items of a wave in
@@ -528,16 +524,15 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
     float (*s_up)[NW][64] = reinterpret_cast<float (*)[NW][64]>(smem_pair + P::lds_h);           // [2]
     float (*s_up2)[64] = reinterpret_cast<float (*)[64]>(smem_pair + P::lds_h + 2 * NW * 64 * sizeof(float));
     int &s_fail = *reinterpret_cast<int *>(smem_pair + P::lds_h + P::lds_up);
-    int &s_near = *reinterpret_cast<int *>(smem_pair + P::lds_h + P::lds_up + 4);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
-    // Workgroup ids go round-robin over the 8 XCDs: ids b and b + 8 land on the same one.  With the weights in registers
-    // (d_g = 256) the members of a pair are 8 apart, so that both sit behind one L2 (2 % faster at config 2; ids past
-    // the last pair have nothing to do).  With streamed weights (d_g = 512) they are neighbours instead, so that an
-    // XCD's L2 serves one half of W_hh only: at config 5, 8.8 against 9.7 ms.
-    const int xcd = blockIdx.x & 7, row = blockIdx.x >> 3;
-    const int member = UT == 1 ? row & 1 : blockIdx.x & 1, gid = UT == 1 ? (row >> 1) * 8 + xcd : blockIdx.x >> 1;
+    // The members of a pair are neighbours in the launch order.  Workgroups are started in that order, so whatever
+    // else holds compute units, a member that is running finds its partner next in line for the first unit that
+    // frees up: a launch that does not fit the chip at once still completes pair by pair.  (Neighbouring ids sit
+    // on different XCDs, so the exchange always takes the write-through path below; at d_g = 512 this also means
+    // that an XCD's L2 serves one half of W_hh only.)
+    const int member = blockIdx.x & 1, gid = blockIdx.x >> 1;
     const int gpl = (a.BH + 15) / 16;
     if (gid >= a.L * gpl) return;
     const int l = gid / gpl, grp = gid % gpl;
@@ -577,17 +572,6 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
     const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(xbase, (uint32_t)nb * G::NW * G::UT * 4096 - (uint32_t)tile0 * 4096);
     const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)gid * P::exch_bytes, P::exch_bytes);
 
-    // Which L2 does the partner sit behind?  Each member leaves the id of its XCC (stamped all-ones, which no step
-    // uses) in the first 16 bytes of its wave 0's odd-parity slot, which the steps reach only after both have read it.
-    // Members behind the same L2 publish with plain stores (the L2 is where their device-scope loads meet them: 0.59
-    // instead of 0.92 us per exchange in isolation); otherwise the stores write through, as device scope requires.
-    const uint32_t my_xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20);        // HW_REG_XCC_ID
-    constexpr uint32_t kHello = 0xFFFFFFFFu;
-    if (tid == 0) {
-        const u32x4_t hello = {my_xcc, kHello, my_xcc, kHello};
-        __builtin_amdgcn_raw_buffer_store_b128(hello, e_rsrc, 0, (int)(((2 + member) * NW) * P::slot_bytes), 16);
-    }
-
     float c_reg[UT][4], ws_own[UT][4], ws_par[UT][4];
     f16_t *h_own = s_h + (size_t)n * HP + tile0 * 16 + 4 * g4;       // + (buf*2 + plane)*16*HP + ut*16
     f16_t *h_par = s_h + (size_t)n * HP + ptile0 * 16 + 4 * g4;
@@ -620,20 +604,7 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
         *reinterpret_cast<f16x4_t *>(h_par + ut * 16) = hi;
         *reinterpret_cast<f16x4_t *>(h_par + 16 * HP + ut * 16) = lo;
     }
-    if (wave == 0) {
-        bool near = false;
-        for (int spin = 0; spin < a.pair_spin_limit; ++spin) {
-            const u32x4_t r = __builtin_amdgcn_raw_buffer_load_b128(e_rsrc, 0, (int)(((2 + (1 - member)) * NW) * P::slot_bytes), 16);
-            asm volatile("" ::: "memory");
-            if (r[1] == kHello && r[3] == kHello) {
-                near = r[0] == my_xcc && r[2] == my_xcc;
-                break;
-            }
-        }
-        if (lane == 0) s_near = near;          // (no answer within the bound: write through; the step waits will expire too)
-    }
     __syncthreads();
-    const bool near = s_near != 0 && !a.pair_write_through;
 
     // one look at the partner wave's slot `par` (device-scope loads; their results are examined later)
     struct Look { u32x4_t v[UT][2]; };
@@ -804,14 +775,9 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
             const uint32_t stamp = (uint32_t)tt + 1;
             const uint32_t off = (uint32_t)((cur * 2 + member) * NW + wave) * P::slot_bytes + ut * 2048;
             const u32x4_t l0 = {hi2.x, stamp, hi2.y, stamp}, l1 = {lo2.x, stamp, lo2.y, stamp};
-            if (member != a.pair_mute) {
-                if (near) {
-                    __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 0);
-                } else {
-                    __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
-                    __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
-                }
+            if (member != a.pair_mute) {       // device scope: the stores write through to where the partner's loads look
+                __builtin_amdgcn_raw_buffer_store_b128(l0, e_rsrc, (int)lane16, (int)off, 16);
+                __builtin_amdgcn_raw_buffer_store_b128(l1, e_rsrc, (int)lane16, (int)(off + 1024), 16);
             }
         }
         ask(cur, ka);                // the partner is about to publish the same step
@@ -840,6 +806,7 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
 #pragma unroll
             for (int r = 0; r < 4; ++r) a.c[s * DG + (tile0 + ut) * 16 + 4 * g4 + r] = failed ? __builtin_nanf("") : c_reg[ut][r];
     }
+    if (failed && tid == 0) __hip_atomic_store(a.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // sticky: the caller's to clear
     if (failed && tid < 16 && live) {
         for (int t = 0; t < nb; ++t) {
             a.util[s * a.N_cap + t0 + t] = __builtin_nanf("");
@@ -848,48 +815,68 @@ __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, 
     }
 }
 
+// One-time launch attributes (LDS beyond 64 KiB), per kernel instance and device: a bit per device id.
+template <int DG>
+static hipError_t set_attributes_once()
+{
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (uint64_t)1 << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_kernel<DG>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)Res<DG>::lds);
+    if (e != hipSuccess) return e;
+    // (the in-projection's staged rows pass 64 KiB at d = 128)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128, kTT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
+    if (e != hipSuccess) return e;
+    if constexpr (DG == 256 || DG == 512) {
+        static_assert(PairGeo<DG>::exch_bytes == (DG / 256) * 65536, "the scratch planner's figure");
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_pair_kernel<DG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)PairGeo<DG>::lds);
+        if (e != hipSuccess) return e;
+    }
+    done.fetch_or(bit, std::memory_order_release);
+    return hipSuccess;
+}
+
+// Weight preparation: W_ih into fragment order and the partial maxima of |W_hh| (one launch), then W_hh scaled,
+// converted and re-laid (a second one, which needs the maxima).  What it leaves depends on the weights alone.
+template <int DG>
+static hipError_t prepare_dg(const LstmArgs &a, hipStream_t st)
+{
+    const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
+    const int nb_wih = (int)((frags_i + 255) / 256);
+    const dim3 grid_p((unsigned)(nb_wih + a.L * kScaleBlocks));
+    if (a.d == 64)
+        hipLaunchKernelGGL((lstm_prep_kernel<DG, 64>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
+                           const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
+    else
+        hipLaunchKernelGGL((lstm_prep_kernel<DG, 128>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
+                           const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
+    // W_hh fragments: 16 bytes per thread and turn, about 4 turns per packing workgroup
+    const size_t frags_h = (size_t)a.L * 4 * DG * DG / 8;
+    const size_t want = (frags_h + (size_t)4 * Geo<DG>::THREADS - 1) / ((size_t)4 * Geo<DG>::THREADS);
+    hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)(want > 4096 ? 4096 : want)), dim3(Geo<DG>::THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
 template <int DG>
 static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
 {
     const int gpl = (a.BH + 15) / 16;
     const unsigned groups = (unsigned)(a.L * gpl);
     const size_t lds = Res<DG>::lds;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_kernel<DG>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = set_attributes_once<DG>();
+    if (e != hipSuccess) return e;
+    if (!a.prepared) {
+        e = prepare_dg<DG>(a, st);
         if (e != hipSuccess) return e;
-        // (the in-projection's staged rows pass 64 KiB at d = 128)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_inproj_kernel<DG, 128, kTT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
-        if (e != hipSuccess) return e;
-        if constexpr (DG == 256 || DG == 512) {
-            static_assert(PairGeo<DG>::exch_bytes == (DG / 256) * 65536, "the scratch planner's figure");
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_pair_kernel<DG>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)PairGeo<DG>::lds);
-            if (e != hipSuccess) return e;
-        }
-        attr_set = true;
     }
-    {
-        const size_t frags_i = (size_t)a.L * 4 * DG * 2 * a.d / 8;
-        const int nb_wih = (int)((frags_i + 255) / 256);
-        const dim3 grid_p((unsigned)(nb_wih + a.L * kScaleBlocks));
-        if (a.d == 64)
-            hipLaunchKernelGGL((lstm_prep_kernel<DG, 64>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
-                               const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
-        else
-            hipLaunchKernelGGL((lstm_prep_kernel<DG, 128>), grid_p, dim3(256), 0, st, static_cast<const bf16_t *>(a.W_ih),
-                               const_cast<bf16x8_t *>(a.wih_packed), static_cast<const bf16_t *>(a.W_hh), a.whh_max_bits, a.L, nb_wih);
-    }
-    // W_hh fragments of the whole call: 16 bytes per thread and turn, about 4 turns per packing workgroup
-    const size_t frags_h = (size_t)a.L * 4 * DG * DG / 8;
     if constexpr (DG == 256) {
-        if (a.fused) {
-            const size_t want = (frags_h + (size_t)4 * Geo<DG>::THREADS - 1) / ((size_t)4 * Geo<DG>::THREADS);
-            hipLaunchKernelGGL((lstm_pack_whh_kernel<DG>), dim3((unsigned)(want > 4096 ? 4096 : want)), dim3(Geo<DG>::THREADS), 0, st, a);
-            return launch_lstm_fused(a, st);
-        }
+        if (a.fused) return launch_lstm_fused(a, st);
     }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
@@ -897,25 +884,18 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         const bool small = (size_t)groups * ((nb + kTT - 1) / kTT) < 256;
         const int tt = small ? 2 : kTT;
         const int ny_proj = (nb + tt - 1) / tt;
-        int ny_pack = 0;
-        if (t0 == a.c0) {
-            const size_t want = (frags_h + (size_t)4 * Geo<DG>::THREADS - 1) / ((size_t)4 * Geo<DG>::THREADS);
-            ny_pack = (int)((want + groups - 1) / groups);
-            if (ny_pack > 4096) ny_pack = 4096;
-        }
-        const dim3 grid_in(groups, (unsigned)(ny_proj + ny_pack));
+        const dim3 grid_in(groups, (unsigned)ny_proj);
         const size_t lds_in = (size_t)tt * 16 * (2 * a.d + 8) * sizeof(bf16_t);
         if (a.d == 64) {
-            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
-            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 64, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
         } else {
-            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
-            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb, ny_proj);
+            if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
+            else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
         }
         if constexpr (DG == 256 || DG == 512) {
             if (a.exch_bytes) {
-                const unsigned pair_grid = DG == 256 ? 16 * ((groups + 7) / 8) : 2 * groups;      // (the kernel's two id orders)
-                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(pair_grid), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
+                hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
                 continue;
             }
         }
@@ -931,6 +911,17 @@ hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st)
     case 128: return launch_dg<128>(a, st);
     case 256: return launch_dg<256>(a, st);
     case 512: return launch_dg<512>(a, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st)
+{
+    switch (a.d_g) {
+    case 64: return prepare_dg<64>(a, st);
+    case 128: return prepare_dg<128>(a, st);
+    case 256: return prepare_dg<256>(a, st);
+    case 512: return prepare_dg<512>(a, st);
     default: return hipErrorInvalidValue;
     }
 }

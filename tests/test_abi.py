@@ -34,11 +34,10 @@ def test_library_exports_every_declared_symbol():
 
 def test_debug_pair_wait_validation():
     L = kb.lib()
-    assert L.kvev_debug_pair_wait(0, -1, 0) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(16, 2, 0) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(16, -2, 0) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(16, -1, 2) == kb.ERR_INVALID_ARG
-    assert L.kvev_debug_pair_wait(1 << 22, -1, 0) == kb.OK      # the defaults
+    assert L.kvev_debug_pair_wait(0, -1) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, 2) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(16, -2) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_pair_wait(1 << 22, -1) == kb.OK      # the defaults
     assert L.kvev_debug_lstm_fused_min_groups(-1) == kb.ERR_INVALID_ARG
     big = kb.make_shape(synth.CONFIGS[3])
     small = kb.make_shape(synth.CONFIGS[2])
@@ -112,6 +111,22 @@ def test_pointer_range_and_mode_validation():
     assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 4, 4, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.OK
     lw0 = kb.LstmW(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000)
     assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw0), 0, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 0, 1, odd, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_INVALID_ARG   # h misaligned
+    assert L.kvev_lstm_gate(r, FAKE, FAKE, ctypes.byref(lw), 0, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_WORKSPACE
+    # weights prepared once
+    need = kb.workspace_bytes(kb.OP_LSTM_PREPARE, sh, 0)
+    assert need == 4 * 256 * (256 + 256) * 2 + 256                      # packed W_hh + W_ih, one layer, and the maxima
+    assert L.kvev_lstm_prepare(r, None, FAKE, need, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_prepare(r, ctypes.byref(lw0), FAKE, need, None) == kb.ERR_INVALID_ARG
+    assert L.kvev_lstm_prepare(r, ctypes.byref(lw), None, need, None) == kb.ERR_WORKSPACE
+    assert L.kvev_lstm_prepare(r, ctypes.byref(lw), FAKE, need - 1, None) == kb.ERR_WORKSPACE
+    f32 = _shape(dtype=kb.F32)
+    assert kb.workspace_bytes(kb.OP_LSTM_PREPARE, f32, 0) == 0
+    assert L.kvev_lstm_prepare(ctypes.byref(f32), ctypes.byref(lw), None, 0, None) == kb.OK      # nothing to prepare
+    assert L.kvev_lstm_gate_prepared(r, FAKE, FAKE, ctypes.byref(lw), None, 0, 0, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == kb.ERR_WORKSPACE
+    assert L.kvev_lstm_gate_prepared(r, FAKE, FAKE, ctypes.byref(lw), FAKE, need, 0, 1, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.ERR_WORKSPACE
+    assert L.kvev_lstm_gate_prepared(r, FAKE, FAKE, ctypes.byref(lw), FAKE, need, 3, 3, FAKE, FAKE, FAKE, FAKE, None, 0, None) == kb.OK
+    assert (kb.workspace_bytes(kb.OP_LSTM_GATE, sh, 128) - kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, sh, 128)) == need
     # select
     assert L.kvev_select(r, FAKE, None, 9, 4, 0.0, 4, FAKE, FAKE, None) == kb.ERR_UNSUPPORTED
     assert L.kvev_select(r, None, None, kb.SELECT_TOPK, 4, 0.0, 4, FAKE, FAKE, None) == kb.ERR_INVALID_ARG

@@ -302,8 +302,9 @@ def test_lstm_gate_single_kernel_form(cfg):
 
 def test_lstm_pair_wait_expires_cleanly():
     """The paired recurrence (d_g = 256, few groups) with one member's publications withheld and a tiny bound on
-    the polls: both workgroups give up, every kernel ends normally, the launch's scores and cell state are NaN,
-    and the next call (defaults restored) is unaffected."""
+    the polls: both workgroups give up, every kernel ends normally, the launch's scores and cell state are NaN and
+    the status word at the head of the workspace is set; it stays set until the caller clears it, and the next call
+    (defaults restored) computes as usual."""
     cfg = _cfg(151, "bf16", d=64, T=320, C=32, d_g=256, L=1, B=1, H=5)
     N = cfg.T // cfg.C
     w = synth.make_weights(cfg, "cpu")
@@ -311,8 +312,11 @@ def test_lstm_pair_wait_expires_cleanly():
     sh = kb.make_shape(cfg, N_cap=N)
     lead = (cfg.L, cfg.B, cfg.H)
     gw = dev(w)
-    ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
     Kb, Vb = Kbar.cuda(), Vbar.cuda()
+    ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+
+    def status():
+        return int(ws[:4].view(torch.int32).item())
 
     def run():
         h = torch.zeros(lead + (cfg.d_g,), device="cuda")
@@ -323,24 +327,76 @@ def test_lstm_pair_wait_expires_cleanly():
         torch.cuda.synchronize()
         return h, c, util, gate
 
+    assert status() == 0
     for mute in (1, 0):
+        ws[:4].zero_()
         kb.kvev_debug_pair_wait(64, mute)
         try:
             h, c, util, gate = run()
         finally:
             kb.kvev_debug_pair_wait()
         assert torch.isnan(util).all() and torch.isnan(gate).all() and torch.isnan(c).all()
+        assert status() == 1
     h, c, util, gate = run()
+    assert status() == 1                 # sticky: a good call does not hide an earlier failure
+    ws[:4].zero_()
+    h, c, util, gate = run()
+    assert status() == 0
     rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
     assert np.abs(util.cpu().numpy() - ru).max() <= SCORE_TOL
     assert np.abs(c.cpu().numpy() - rc).max() <= 2 * SCORE_TOL
-    # the publication through write-through stores (what pairs that do not share an L2 use) gives the same bits
-    kb.kvev_debug_pair_wait(write_through=1)
+
+
+PREPARED_CASES = [
+    (_cfg(191, "bf16", d=128, T=384, C=32, d_g=256, L=1, B=1, H=20), 0),     # pairs of workgroups
+    (_cfg(192, "bf16", d=64, T=256, C=32, d_g=256, L=13, B=5, H=16), 0),     # one workgroup per group
+    (_cfg(193, "bf16", d=128, T=256, C=32, d_g=256, L=2, B=2, H=20), 1),     # the single-kernel form
+    (_cfg(194, "bf16", d=64, T=320, C=32, d_g=128, L=2, B=1, H=9), 0),       # all of W_hh in LDS
+    (_cfg(195, "bf16", d=128, T=256, C=32, d_g=512, L=1, B=1, H=18), 0),     # widest gate, on pairs
+    (_cfg(196, "f32", d=64, T=256, C=32, d_g=48, L=1, B=2, H=3), 0),         # nothing to prepare: the generic kernels
+]
+
+
+@pytest.mark.parametrize("cfg,fused", PREPARED_CASES, ids=lambda c: getattr(c, "name", str(c)))
+def test_lstm_prepare_once_gate_many(cfg, fused):
+    """Weights packed once by kvev_lstm_prepare serve any number of kvev_lstm_gate_prepared calls (here a stream cut
+    into three), each bit-identical to kvev_lstm_gate, which packs on every call (Eq. 3)."""
+    N = cfg.T // cfg.C
+    w = synth.make_weights(cfg, "cpu")
+    Kbar, Vbar = _summaries(cfg, N)
+    sh = kb.make_shape(cfg, N_cap=N)
+    lead = (cfg.L, cfg.B, cfg.H)
+    gw = dev(w)
+    lw = kb.lstm_weights(gw)
+    Kb, Vb = Kbar.cuda(), Vbar.cuda()
+    if fused:
+        kb.kvev_debug_lstm_fused_min_groups(1)
     try:
-        h2, c2, util2, gate2 = run()
+        ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+        wsp = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, sh, N))
+        packed = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_PREPARE, sh, 0))
+        outs = []
+        for prepared in (False, True):
+            h = torch.zeros(lead + (cfg.d_g,), device="cuda")
+            c = torch.zeros_like(h)
+            util = torch.zeros(lead + (N,), device="cuda")
+            gate = torch.zeros_like(util)
+            if prepared:
+                kb.kvev_lstm_prepare(sh, lw, packed)
+            for a, b in ((0, 2), (2, 5), (5, N)):
+                if prepared:
+                    kb.kvev_lstm_gate_prepared(sh, Kb, Vb, lw, packed, a, b, h, c, util, gate, wsp)
+                else:
+                    kb.kvev_lstm_gate(sh, Kb, Vb, lw, a, b, h, c, util, gate, ws)
+            torch.cuda.synchronize()
+            outs.append((h, c, util, gate))
     finally:
-        kb.kvev_debug_pair_wait()
-    assert torch.equal(util, util2) and torch.equal(gate, gate2) and torch.equal(h, h2) and torch.equal(c, c2)
+        if fused:
+            kb.kvev_debug_lstm_fused_min_groups(0)
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+    _, _, ru, _ = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
+    assert np.abs(outs[1][2].cpu().numpy() - ru).max() <= SCORE_TOL
 
 
 def _run_cold(cfg, t, g):
