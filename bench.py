@@ -702,6 +702,8 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="rotating input sets (0: enough to exceed 512 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the sub-records of the other configurations")
+    ap.add_argument("--lean", action="store_true", help="profiling aid: the timed cold steps, the steady-state and dense "
+                                                        "lines only (no threshold, eviction, aggregator sections)")
     ap.add_argument("--only", default="", help="profiling aid: run only this stage in the timed loop "
                                                  "(pool|gate|select|attend|dense)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -766,6 +768,7 @@ def main():
         out["rooflines"] = rooflines + extra
         if b.cost["dense"]["bytes"] < (1 << 30):
             out["cold_step_graph_replay"] = b.graph_replays(args.steps, steady)
+    if not args.only and not args.lean:
         out["threshold_mode"] = b.threshold_mode(args.steps, dense["us_per_step"])
         out["eviction"] = b.eviction(args.steps)
         from paper_2509_21354_amd import cost_model as cm

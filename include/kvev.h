@@ -76,8 +76,8 @@ typedef struct { const void *W1, *b1, *W2, *b2; } kvev_mlp_w;
  * b_ih, b_hh [L,4d_g]   scalar utility head  w_s [L,d_g]  b_s [L]. */
 typedef struct { const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s; } kvev_lstm_w;
 
-/* Eq. 2 (chunk aggregation; section 3.3 "each completed chunk is aggregated
- * ... by a 2-layer MLP").  For every sequence and every chunk c in
+/* Eq. 2 (chunk aggregation; section 3.3: a chunk is aggregated once it is
+ * complete, by a two-layer MLP).  For every sequence and every chunk c in
  * [chunk_begin, chunk_end):  xbar = mean of the chunk's C keys;
  * Kbar[c] = W2 * GELU(W1 * xbar + b1) + b2 with the K weights (exact erf GELU),
  * the same for V with the V weights; KVEV_POOL_MEAN stores xbar itself and
@@ -220,7 +220,7 @@ int kvev_dense_attention(const kvev_shape *shape, const void *Q, int Tq, const v
                          void *stream);
 
 /* Physical eviction (sections 3.2-3.3: a chunk that is not kept is discarded;
- * section 3.4: the cache shrinks by n / (W + M)).  Per sequence a compact store
+ * the end of section 3.3: the cache shrinks by n / (W + M)).  Per sequence a compact store
  * holds at most k kept summaries, ascending by chunk id:
  *   Kc, Vc    [L,B,H,k_cap,d]  storage dtype     chunk_id [L,B,H,k_cap] int32
  *   util_c    [L,B,H,k_cap]    fp32 scores        count    [L,B,H] int32 (in/out;

@@ -10,8 +10,8 @@
  *
  * Every step follows the paper's own statement of the method:
  *   partition  section 3.2 (non-overlapping fixed-length chunks, temporal
- *              order) and section 3.3 ("each completed chunk")
- *   pool       Eq. 2, MLP_K / MLP_V; section 3.3 ("2-layer MLP"); Eq. 6's
+ *              order) and section 3.3 (only chunks that are complete are aggregated)
+ *   pool       Eq. 2, MLP_K / MLP_V; section 3.3 (the aggregator is a two-layer MLP); Eq. 6's
  *              term 4*d_sum*d per chunk fixes "once per chunk"
  *   gate       Eq. 3, an LSTM over [Kbar_t, Vbar_t] carrying h_t and emitting
  *              a score s_t in [0,1]
@@ -470,7 +470,7 @@ int kvo_gated_attention(int dtype, int L, int B, int H, int d, int T, int T_cap,
     return rc;
 }
 
-/* ---------- physical eviction (sections 3.2-3.3, memory ratio of section 3.4) ----
+/* ---------- physical eviction (sections 3.2-3.3; the memory ratio closes section 3.3) ----
  * Chunks that are not kept are discarded, so what stays resident per sequence is
  * a compact store of at most k summaries plus the raw window.  The store holds,
  * ascending by chunk id: chunk_id [S,k_cap], util_c [S,k_cap], Kc, Vc [S,k_cap,d],

@@ -1,4 +1,4 @@
-"""The paper's closed-form cost model (section 3.4, Eq. 4-7), for reporting beside
+"""The paper's closed-form cost model (section 3.3, Eq. 4-7), for reporting beside
 measured numbers.  Nothing on the GPU path depends on it.
 
 Symbols as in the paper: B batch, n cached tokens, d_model, H heads, d_k head
@@ -44,7 +44,7 @@ def speed_up(flops_base: float, flops_ffn_: float, flops_kv_eff: float) -> float
 
 
 def memory_ratio(n: int, W: int, M: float) -> float:
-    """Section 3.4, last paragraph: rows of cache kept, n / (W + M)."""
+    """Section 3.3, last paragraph: rows of cache kept, n / (W + M)."""
     return n / (W + M)
 
 

@@ -1,5 +1,5 @@
 // Physical eviction (sections 3.2-3.3 of the paper: a chunk that is not kept is
-// discarded, which is where the memory ratio n / (W + M) of section 3.4 comes
+// discarded, which is where the memory ratio n / (W + M) of section 3.3 comes
 // from).  Per sequence a compact store holds at most k summaries, ascending by
 // chunk id, with their ids and scores.  Freshly scored chunks (ids above every
 // id in the store) are merged in and the best min(k, count + n_new) under the

@@ -1,4 +1,4 @@
-"""The closed-form cost model of section 3.4 (Eq. 4-7): reporting only.
+"""The closed-form cost model of section 3.3 (Eq. 4-7): reporting only.
 
 The paper prints intermediate numbers in section 4.1 (tests/golden/cost_model_section_4_1.txt).
 Eq. 7 applied to those printed numbers reproduces its 1.61x; Eq. 4 and Eq. 5 evaluated at the

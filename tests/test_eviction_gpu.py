@@ -1,4 +1,4 @@
-"""Physical eviction on the GPU (sections 3.2-3.4): the compact store kept as the running top-k,
+"""Physical eviction on the GPU (sections 3.2-3.3): the compact store kept as the running top-k,
 attention over store + resident window, and a stream that never holds more than k + window rows,
 checked against the oracle and against the non-evicting path."""
 import numpy as np

@@ -565,7 +565,7 @@ def test_compact_attention_equals_gated_attention_on_the_gathered_rows(oracle):
         assert (oracle.compact_attention(Qf, Kr, Vr, wl, Kc, Vc, r["count"], causal=1, win_first=first) == Oc).all()
         with pytest.raises(ValueError):
             oracle.compact_attention(t["Q"], Kr, Vr, wl, Kc, Vc, r["count"], win_first=cap)
-        # resident rows: k + window instead of T (the memory ratio of section 3.4)
+        # resident rows: k + window instead of T (the memory ratio of section 3.3)
         assert Kc.shape[3] - 1 + Kw.shape[3] == cfg.k + cfg.T - win0 < cfg.T
 
 
