@@ -605,9 +605,11 @@ def grouped_query_cfg3(torch, kb, synth, gated_us_32_heads):
 
 
 def calibrate_stream(torch, kb):
-    """Reference streams for the HBM-bound kernels: a pure read of config 3's pooling footprint (two 17 GB tensors
-    summed by torch, 4 bytes out per launch) and a read with 3 % written (the pooling kernel in mean mode reads
-    every raw row and writes one row per chunk of 32: the same read/write mix as the MLP mode, no matrix work)."""
+    """Reference streams for the HBM-bound kernels, on config 3's footprint.  A plain streaming kernel (one workgroup
+    per 256 KiB tile, no arithmetic: kvev_debug_stream_probe) reads 17 GB with no writes, then with 1.5 % and 3 % of
+    the bytes written back: what the machine gives the memory pattern of chunk pooling (which writes one summary row
+    per chunk of 32 rows: 3 %).  Beside them the library's own pure reader (dense decode attention), pooling in mean
+    mode (the same read / write mix as the MLP mode, no matrix work) and a plain device copy."""
     from paper_2509_21354_amd import synth
     cfg = synth.CONFIGS[3]
     kv = synth.make_qkv(cfg, "cuda")
@@ -625,19 +627,25 @@ def calibrate_stream(torch, kb):
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
     nbytes = kv["K"].numel() * 2
-    kflat = kv["K"].view(torch.int32).view(-1)
-    t_read = t_of(lambda: torch.max(kflat), 5)
-    out["pure_read_torch_max"] = {"bytes": nbytes, "us": round(t_read, 1), "GBps": round(nbytes / t_read / 1e3, 1)}
-    t_dense = t_of(lambda: kb.kvev_dense_attention(st.shape, kv["Q"], 1, kv["K"], kv["V"], torch.empty_like(kv["Q"]), st.ws_attn), 5)
+    tile = 256 << 10
+    dst = torch.empty((nbytes // tile) * 8192 + 16, dtype=torch.uint8, device="cuda")
+    for name, wb in (("probe_pure_read", 0), ("probe_read_plus_1.5pct_write", 4096), ("probe_read_plus_3pct_write", 8192)):
+        t = t_of(lambda: kb.kvev_debug_stream_probe(kv["K"], tile, dst, wb), 5)
+        out[name] = {"bytes_read": nbytes, "bytes_written": (nbytes // tile) * wb, "us": round(t, 1),
+                     "read_GBps": round(nbytes / t / 1e3, 1), "total_GBps": round((nbytes + (nbytes // tile) * wb) / t / 1e3, 1)}
+    del dst
+    O = torch.empty_like(kv["Q"])
+    t_dense = t_of(lambda: kb.kvev_dense_attention(st.shape, kv["Q"], 1, kv["K"], kv["V"], O, st.ws_attn), 5)
     db = costs(cfg)["dense"]["bytes"]
-    out["pure_read_dense_attention"] = {"bytes": db, "us": round(t_dense, 1), "GBps": round(db / t_dense / 1e3, 1)}
-    t_mean = t_of(lambda: kb.kvev_chunk_pool(st.shape, kv["K"], kv["V"], kb.POOL_MEAN, None, None, 0, cfg.N, st.Kbar, st.Vbar, st.ws), 5)
+    out["dense_decode_attention_pure_read"] = {"bytes": db, "us": round(t_dense, 1), "GBps": round(db / t_dense / 1e3, 1)}
     pb = costs(cfg)["pool"]["bytes"]
-    out["read_plus_3pct_write_pool_mean"] = {"bytes": pb, "us": round(t_mean, 1), "GBps": round(pb / t_mean / 1e3, 1)}
+    for name, mode in (("pool_mean_read_plus_3pct_write", kb.POOL_MEAN),):
+        t = t_of(lambda: kb.kvev_chunk_pool(st.shape, kv["K"], kv["V"], mode, None, None, 0, cfg.N, st.Kbar, st.Vbar, st.ws), 5)
+        out[name] = {"bytes": pb, "us": round(t, 1), "GBps": round(pb / t / 1e3, 1)}
     src = kv["K"].view(-1)
-    dst = kv["V"].view(-1)
-    t_copy = t_of(lambda: dst.copy_(src), 5)
-    out["copy_read_equals_write"] = {"bytes": 2 * nbytes, "us": round(t_copy, 1), "GBps": round(2 * nbytes / t_copy / 1e3, 1)}
+    dstc = kv["V"].view(-1)
+    t_copy = t_of(lambda: dstc.copy_(src), 5)
+    out["device_copy_read_equals_write"] = {"bytes": 2 * nbytes, "us": round(t_copy, 1), "GBps": round(2 * nbytes / t_copy / 1e3, 1)}
     return out
 
 

@@ -174,7 +174,12 @@ int kvev_select(const kvev_shape *shape, const float *util, const float *gate, i
  * n' = W + M).  For every sequence and each of its Tq queries the attended
  * rows are Kbar[idx[0..count)] / Vbar[...] followed by the raw tokens
  * win0 .. T-1 of K / V; O = softmax(q . keys^T / sqrt(d)) . values with fp32
- * scores, softmax and accumulation, rounded once to the storage dtype.  With
+ * scores, softmax and accumulation, rounded once to the storage dtype.  (One
+ * more rounding on the matrix-core path, which bf16 storage takes when a
+ * key-value sequence has 16 or more queries: the softmax weights enter the
+ * product with the values rounded to bf16, 8 significant bits, while the
+ * normaliser sums them unrounded; the result stays within the bf16 bar, see the
+ * measured figures in the parity report of the tests.)  With
  * causal == 0 the Tq queries see the whole cache and not each other; with
  * causal == 1 (strict causality, section 3.2) they ARE the last Tq cached tokens,
  * query i at position T - Tq + i, and each sees the kept summaries and the raw

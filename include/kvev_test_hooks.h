@@ -7,6 +7,8 @@
 #ifndef KVEV_TEST_HOOKS_H
 #define KVEV_TEST_HOOKS_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -27,6 +29,16 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member);
  * run that form on a shape the CPU oracle finishes in seconds; 0 restores the
  * default.  Errors: INVALID_ARG for a negative value. */
 int kvev_debug_lstm_fused_min_groups(int min_groups);
+
+/* Calibration of the memory system for the benchmark's roofline notes (bench.py
+ * --calibrate-stream): a plain streaming kernel, one workgroup per tile, reads
+ * src_bytes of device memory in tiles of tile_bytes (a multiple of 4096 that
+ * divides src_bytes) and writes write_bytes_per_tile (a multiple of 16, 0 =
+ * none) per tile to dst (device memory of at least tiles * write_bytes_per_tile
+ * bytes, 16 at least).  The memory pattern of chunk pooling without its
+ * arithmetic.  Enqueued on `stream`; errors: INVALID_ARG. */
+int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, void *dst, size_t dst_bytes,
+                            int write_bytes_per_tile, void *stream);
 
 #ifdef __cplusplus
 }

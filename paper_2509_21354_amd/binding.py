@@ -29,7 +29,7 @@ OP_LSTM_PREPARE, OP_LSTM_GATE_PREPARED = 6, 7
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_lstm_prepare", "kvev_lstm_gate_prepared", "kvev_select", "kvev_gated_attention",
            "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
            "kvev_status_string", "kvev_last_hip_error", "kvev_version")
-TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups")      # include/kvev_test_hooks.h
+TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups", "kvev_debug_stream_probe")      # include/kvev_test_hooks.h
 
 
 class Shape(ctypes.Structure):
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_debug_pair_wait.restype = ci
         L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
         L.kvev_debug_lstm_fused_min_groups.restype = ci
+        L.kvev_debug_stream_probe.argtypes = [vp, sz, ci, vp, sz, ci, vp]
+        L.kvev_debug_stream_probe.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
         L.kvev_last_hip_error.restype = ctypes.c_char_p
@@ -140,6 +142,12 @@ def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> No
 
 def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:
     _check(lib().kvev_debug_lstm_fused_min_groups(min_groups), "kvev_debug_lstm_fused_min_groups")
+
+
+def kvev_debug_stream_probe(src: torch.Tensor, tile_bytes: int, dst: torch.Tensor, write_bytes_per_tile: int) -> None:
+    st = lib().kvev_debug_stream_probe(_ptr(src), src.numel() * src.element_size(), tile_bytes, _ptr(dst),
+                                       dst.numel() * dst.element_size(), write_bytes_per_tile, _stream())
+    _check(st, "kvev_debug_stream_probe")
 
 
 def workspace_bytes(op: int, shape: Shape, n: int, k_cap: int = 0) -> int:

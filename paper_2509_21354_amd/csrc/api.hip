@@ -504,6 +504,20 @@ int kvev_debug_lstm_fused_min_groups(int min_groups)
     return KVEV_OK;
 }
 
+int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, void *dst, size_t dst_bytes,
+                            int write_bytes_per_tile, void *stream)
+{
+    if (!src || !dst || !aligned16(src) || !aligned16(dst)) return KVEV_ERR_INVALID_ARG;
+    if (tile_bytes < 4096 || tile_bytes % 4096 != 0 || src_bytes % (size_t)tile_bytes != 0) return KVEV_ERR_INVALID_ARG;
+    if (write_bytes_per_tile < 0 || write_bytes_per_tile % 16 != 0) return KVEV_ERR_INVALID_ARG;
+    const size_t tiles = src_bytes / (size_t)tile_bytes;
+    if (tiles > ((size_t)1 << 31) - 1) return KVEV_ERR_INVALID_ARG;
+    const size_t need = write_bytes_per_tile ? tiles * (size_t)write_bytes_per_tile : 16;
+    if (dst_bytes < need) return KVEV_ERR_INVALID_ARG;
+    hipError_t e = launch_stream_probe(src, tiles, tile_bytes, dst, write_bytes_per_tile, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVEV_OK : hip_fail(e);
+}
+
 size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
 {
     if (check_shape(sh, op != KVEV_OP_COMPACT_ATTENTION) != KVEV_OK || n < 0) return 0;

@@ -95,6 +95,7 @@ size_t pool_token_mfma_lds(int d, int d_sum);                            // its 
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
 hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st);       // bf16: the packed weights alone
+hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, hipStream_t st);   // calibration
 hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

@@ -17,6 +17,15 @@ def vals(x):
     return orc.from_bits(orc.to_np(x))
 
 
+def worst_rel_error(got, ref):
+    """max over elements of |got - ref| / max(|ref|, rms(ref)): the quantity the bf16 bar (2e-2) bounds."""
+    g, r = vals(got), vals(ref)
+    if g.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(r * r)))
+    return float((np.abs(g - r) / np.maximum(np.maximum(np.abs(r), rms), 1e-30)).max())
+
+
 def assert_close_storage(got, ref, dtype, what=""):
     """The stated bars: fp32 storage max-abs 1e-4; bf16 storage 'relative 2e-2',
     read per tensor as |got-ref| <= 2e-2 * max(|ref|, rms(ref)) element-wise."""
