@@ -55,7 +55,8 @@ template <int D> struct Fus {
     static constexpr size_t lds_up = (size_t)2 * NW * SEQ * sizeof(float);         // shares of the utility logit
     static constexpr size_t lds_b = (size_t)4 * DG * sizeof(float);                // b_ih + b_hh
     static constexpr size_t lds_w = (size_t)NW * LRES * 4096;
-    static constexpr size_t lds = lds_h + lds_x + lds_up + lds_b + lds_w;
+    static constexpr size_t lds_ub = (size_t)16 * SEQ * sizeof(float);             // utility logits of 16 steps, written out together
+    static constexpr size_t lds = lds_h + lds_x + lds_up + lds_b + lds_w + lds_ub;
     static_assert(lds <= 160 * 1024, "LDS budget of a CU");
 };
 
@@ -72,6 +73,7 @@ __global__ __launch_bounds__(512) void lstm_fused_kernel(LstmArgs a, int t0, int
     float *s_up = reinterpret_cast<float *>(smem_f + F::lds_h + F::lds_x);           // [2][NW][SEQ]
     float *s_bias = reinterpret_cast<float *>(smem_f + F::lds_h + F::lds_x + F::lds_up);
     unsigned char *s_w = smem_f + F::lds_h + F::lds_x + F::lds_up + F::lds_b;
+    float *s_ubuf = reinterpret_cast<float *>(smem_f + F::lds_h + F::lds_x + F::lds_up + F::lds_b + F::lds_w);   // [16][SEQ]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
@@ -144,7 +146,8 @@ __global__ __launch_bounds__(512) void lstm_fused_kernel(LstmArgs a, int t0, int
     auto fetch_x = [&](int tt) {                // step tt of this launch (clamped: the last steps fetch a valid row again)
         const size_t off = (size_t)min(tt, nb - 1) * D;
 #pragma unroll
-        for (int k = 0; k < NP; ++k) xreg[k] = *reinterpret_cast<const u32x4_t *>(xsrc[k] + off);
+        for (int k = 0; k < NP; ++k)      // read once: the hint keeps the stream from pushing the weights out of L2
+            xreg[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(xsrc[k] + off));
     };
     auto stash_x = [&](int ring) {
 #pragma unroll
@@ -212,6 +215,33 @@ __global__ __launch_bounds__(512) void lstm_fused_kernel(LstmArgs a, int t0, int
     read_ops(std::integral_constant<int, 0>{}, 0, 0);
     if constexpr (F::cls(0) == 0) read_wl();
 
+    // The utility logit of chunk c, from the waves' shares in s_up[ub], by wave 0.  Scores are held back in LDS and
+    // leave in runs of 16 chunks (64 bytes per sequence at a time), so that a cache line of the score arrays is written
+    // while it is still in L2 instead of 4 bytes at a time across hundreds of microseconds.
+    auto emit_score = [&](int c, int ub, bool last) {
+        if (lane < SEQ) {
+            float u = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) u += s_up[(ub * NW + w) * SEQ + lane];
+            s_ubuf[(c & 15) * SEQ + lane] = u + b_s;
+        }
+        if ((c & 15) == 15 || last) {
+            const int c_lo = max(t0, c & ~15), sq2 = lane >> 1, half = lane & 1;
+            if (grp * SEQ + sq2 < a.BH) {
+                const size_t s = (size_t)l * a.BH + grp * SEQ + sq2;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int cj = (c & ~15) + half * 8 + j;
+                    if (cj >= c_lo && cj <= c) {
+                        const float u = s_ubuf[(cj & 15) * SEQ + sq2];
+                        a.util[s * a.N_cap + cj] = u;
+                        a.gate[s * a.N_cap + cj] = sigmoid_hw(u);
+                    }
+                }
+            }
+        }
+    };
+
     f32x4_t acc[SB][4];
     float upart[SB] = {0.f, 0.f};
     int ring = 0;                // tt % 3
@@ -252,17 +282,7 @@ __global__ __launch_bounds__(512) void lstm_fused_kernel(LstmArgs a, int t0, int
             if constexpr (i == KX) {
                 // ---- the step's barrier: every wave has published its part of h_{t-1} ----
                 __syncthreads();
-                if (tt > 0 && tid < SEQ) {       // the logit of the step before, from the waves' shares
-                    float u = 0.f;
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) u += s_up[(nxt * NW + w) * SEQ + tid];
-                    u += b_s;
-                    if (grp * SEQ + tid < a.BH) {
-                        const size_t s = (size_t)l * a.BH + grp * SEQ + tid;
-                        a.util[s * a.N_cap + t0 + tt - 1] = u;
-                        a.gate[s * a.N_cap + t0 + tt - 1] = sigmoid_hw(u);
-                    }
-                }
+                if (tt > 0 && wave == 0) emit_score(t0 + tt - 1, nxt, false);       // the logit of the step before
                 read_ops(ic, cur, ring);
             }
             // operands of what comes next are asked for before this item's MFMAs (h of this step only after the barrier)
@@ -319,16 +339,7 @@ __global__ __launch_bounds__(512) void lstm_fused_kernel(LstmArgs a, int t0, int
         ring = ring_next;
     }
     __syncthreads();
-    if (tid < SEQ && grp * SEQ + tid < a.BH) {       // the last step's logit
-        const int ub = (nb - 1) & 1;
-        float u = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) u += s_up[(ub * NW + w) * SEQ + tid];
-        u += b_s;
-        const size_t s = (size_t)l * a.BH + grp * SEQ + tid;
-        a.util[s * a.N_cap + t0 + nb - 1] = u;
-        a.gate[s * a.N_cap + t0 + nb - 1] = sigmoid_hw(u);
-    }
+    if (wave == 0) emit_score(t0 + nb - 1, (nb - 1) & 1, true);       // the last step's logit, and whatever is still held back
 #pragma unroll
     for (int ut = 0; ut < UT; ++ut)
 #pragma unroll
