@@ -490,12 +490,33 @@ def streaming_cfg4(torch, kb, synth):
         e1.record()
         torch.cuda.synchronize()
     t_frame = e0.elapsed_time(e1) * 1e3 / c4.steps
+    O_gated = O4.clone()
+
+    # the same decodes with full-cache attention over everything that has arrived (no pooling, gate or selection)
+    def frame_dense(si):
+        sh4.T = (si + 1) * c4.frame
+        for j in range(c4.decode_per_step):
+            kb.kvev_dense_attention(sh4, q4[si, j], 1, kv4["K"], kv4["V"], O4, s4.ws_attn)
+    for rep in range(2):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for si in range(c4.steps):
+            frame_dense(si)
+        e1.record()
+        torch.cuda.synchronize()
+    t_fd = e0.elapsed_time(e1) * 1e3 / c4.steps
+    O4.copy_(O_gated)
     out["streaming_cfg4"] = {
         "workload": c4.name + f" ({c4.steps} frames of {c4.frame} tokens, {c4.decode_per_step} decoded tokens per frame, "
                               f"cache grows to {c4.T} tokens)",
         "us_per_frame": round(t_frame, 2),
         "decoded_tokens_per_s_per_layer": round(c4.B * c4.decode_per_step / (t_frame * 1e-6), 1),
-        "frames_per_s": round(1e6 / t_frame, 1)}
+        "frames_per_s": round(1e6 / t_frame, 1),
+        "dense_us_per_frame": round(t_fd, 2),
+        "speedup_vs_dense_stream": round(t_fd / t_frame, 2),
+        "note": "the gated frame includes pooling, gating and re-selection of the new frame; the dense frame is the "
+                "same decodes over the whole cache that has arrived, averaged over the growing stream"}
     # the same stream with physical eviction: resident are the compact store (k rows), a ring of W + 2 frames
     # raw rows and the summaries of chunks still inside the window; chunks that leave the window are merged
     # into the store (no re-selection over all candidates), the decodes read store + ring

@@ -10,6 +10,10 @@
 //   lstm_rec_pair_kernel  the same on two workgroups per 16 sequences, each
 //                       with half of the hidden units, for launches small enough
 //                       to be resident at once (further down).
+// Before them, once per set of weights: lstm_prep_kernel (W_ih into fragment
+// order, per-layer scale of W_hh) and lstm_pack_whh_kernel.  Launches with more
+// sequence groups than compute units take one kernel for both halves instead
+// (lstm_fused.hip), which shares the preparation and the helpers of this file.
 //
 // Tiling (both kernels): v_mfma_f32_16x16x32_bf16 with the gate rows as the M
 // side (A operand = weight rows, read straight from global memory / L2 in
@@ -248,8 +252,8 @@ template <int DG> __device__ void pack_whh_blocks(const LstmArgs &a, int block, 
     }
 }
 
-// The same re-layout as a launch of its own, for the single-kernel form of the gate (which has no input-projection
-// launch to ride in).
+// The re-layout of W_hh (fp16, scaled, fragment order) as a launch of its own: part of the weight preparation, which
+// runs once per set of weights (kvev_lstm_prepare) or at the head of a gate call that was handed plain weights.
 template <int DG>
 __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_pack_whh_kernel(LstmArgs a)
 {
