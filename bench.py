@@ -629,7 +629,8 @@ def calibrate_stream(torch, kb):
     """Reference streams for the HBM-bound kernels, on config 3's footprint.  A plain streaming kernel (one workgroup
     per 256 KiB tile, no arithmetic: kvev_debug_stream_probe) reads 17 GB with no writes, then with 1.5 % and 3 % of
     the bytes written back: what the machine gives the memory pattern of chunk pooling (which writes one summary row
-    per chunk of 32 rows: 3 %).  Beside them the library's own pure reader (dense decode attention), pooling in mean
+    per chunk of 32 rows: 3 %); each with plain accesses and with the non-temporal hint on loads and stores (what the
+    library's streaming kernels use).  Beside them the library's own pure reader (dense decode attention), pooling in mean
     mode (the same read / write mix as the MLP mode, no matrix work) and a plain device copy."""
     from paper_2509_21354_amd import synth
     cfg = synth.CONFIGS[3]
@@ -650,10 +651,12 @@ def calibrate_stream(torch, kb):
     nbytes = kv["K"].numel() * 2
     tile = 256 << 10
     dst = torch.empty((nbytes // tile) * 8192 + 16, dtype=torch.uint8, device="cuda")
-    for name, wb in (("probe_pure_read", 0), ("probe_read_plus_1.5pct_write", 4096), ("probe_read_plus_3pct_write", 8192)):
-        t = t_of(lambda: kb.kvev_debug_stream_probe(kv["K"], tile, dst, wb), 5)
-        out[name] = {"bytes_read": nbytes, "bytes_written": (nbytes // tile) * wb, "us": round(t, 1),
-                     "read_GBps": round(nbytes / t / 1e3, 1), "total_GBps": round((nbytes + (nbytes // tile) * wb) / t / 1e3, 1)}
+    for hname, hints in (("plain", 0), ("nontemporal", 3)):
+        for name, wb in (("probe_pure_read", 0), ("probe_read_plus_1.5pct_write", 4096), ("probe_read_plus_3pct_write", 8192)):
+            t = t_of(lambda: kb.kvev_debug_stream_probe(kv["K"], tile, dst, wb, hints), 5)
+            out[f"{name}_{hname}"] = {"bytes_read": nbytes, "bytes_written": (nbytes // tile) * wb, "us": round(t, 1),
+                                      "read_GBps": round(nbytes / t / 1e3, 1),
+                                      "total_GBps": round((nbytes + (nbytes // tile) * wb) / t / 1e3, 1)}
     del dst
     O = torch.empty_like(kv["Q"])
     t_dense = t_of(lambda: kb.kvev_dense_attention(st.shape, kv["Q"], 1, kv["K"], kv["V"], O, st.ws_attn), 5)

@@ -36,9 +36,11 @@ int kvev_debug_lstm_fused_min_groups(int min_groups);
  * divides src_bytes) and writes write_bytes_per_tile (a multiple of 16, 0 =
  * none) per tile to dst (device memory of at least tiles * write_bytes_per_tile
  * bytes, 16 at least).  The memory pattern of chunk pooling without its
- * arithmetic.  Enqueued on `stream`; errors: INVALID_ARG. */
+ * arithmetic.  hints: bit 0 = the loads, bit 1 = the stores carry the
+ * non-temporal hint (what the library's own streaming kernels use); 0 = plain
+ * accesses.  Enqueued on `stream`; errors: INVALID_ARG. */
 int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, void *dst, size_t dst_bytes,
-                            int write_bytes_per_tile, void *stream);
+                            int write_bytes_per_tile, int hints, void *stream);
 
 #ifdef __cplusplus
 }

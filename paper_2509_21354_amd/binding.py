@@ -82,7 +82,7 @@ def lib() -> ctypes.CDLL:
         L.kvev_debug_pair_wait.restype = ci
         L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
         L.kvev_debug_lstm_fused_min_groups.restype = ci
-        L.kvev_debug_stream_probe.argtypes = [vp, sz, ci, vp, sz, ci, vp]
+        L.kvev_debug_stream_probe.argtypes = [vp, sz, ci, vp, sz, ci, ci, vp]
         L.kvev_debug_stream_probe.restype = ci
         L.kvev_status_string.argtypes = [ci]
         L.kvev_status_string.restype = ctypes.c_char_p
@@ -144,9 +144,10 @@ def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:
     _check(lib().kvev_debug_lstm_fused_min_groups(min_groups), "kvev_debug_lstm_fused_min_groups")
 
 
-def kvev_debug_stream_probe(src: torch.Tensor, tile_bytes: int, dst: torch.Tensor, write_bytes_per_tile: int) -> None:
+def kvev_debug_stream_probe(src: torch.Tensor, tile_bytes: int, dst: torch.Tensor, write_bytes_per_tile: int,
+                            hints: int = 0) -> None:
     st = lib().kvev_debug_stream_probe(_ptr(src), src.numel() * src.element_size(), tile_bytes, _ptr(dst),
-                                       dst.numel() * dst.element_size(), write_bytes_per_tile, _stream())
+                                       dst.numel() * dst.element_size(), write_bytes_per_tile, hints, _stream())
     _check(st, "kvev_debug_stream_probe")
 
 

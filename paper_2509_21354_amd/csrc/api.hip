@@ -92,6 +92,7 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 }
 
 // a frame of queries per key-value sequence (all heads of a group count) goes to the matrix cores
+constexpr size_t kStreamBytes = (size_t)256 << 20;     // what the memory-side cache holds
 static bool attn_takes_mq(const kvev_shape *sh, int Tq)
 {
     return sh->dtype == KVEV_BF16 && (int64_t)(sh->H / kv_heads(sh)) * Tq >= 16;
@@ -183,6 +184,8 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     a.T = sh->T; a.T_cap = sh->T_cap; a.N_cap = compact ? k_cap : sh->N_cap; a.k_cap = k_cap;
     a.win0 = win0; a.ring_first = ring_first; a.gated = gated ? 1 : 0;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
+    // rows that no cache can hold until the next call are read with the streaming hint (256 MB: the memory-side cache)
+    a.stream = (size_t)a.S * (size_t)n_rows * sh->d * 2 * (sh->dtype == KVEV_F32 ? 4 : 2) > kStreamBytes ? 1 : 0;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
     hipError_t e = mq ? launch_attn_mq(a, static_cast<hipStream_t>(stream))
                       : launch_attn_decode(a, sh->dtype, static_cast<hipStream_t>(stream));
@@ -505,16 +508,16 @@ int kvev_debug_lstm_fused_min_groups(int min_groups)
 }
 
 int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, void *dst, size_t dst_bytes,
-                            int write_bytes_per_tile, void *stream)
+                            int write_bytes_per_tile, int hints, void *stream)
 {
     if (!src || !dst || !aligned16(src) || !aligned16(dst)) return KVEV_ERR_INVALID_ARG;
     if (tile_bytes < 4096 || tile_bytes % 4096 != 0 || src_bytes % (size_t)tile_bytes != 0) return KVEV_ERR_INVALID_ARG;
-    if (write_bytes_per_tile < 0 || write_bytes_per_tile % 16 != 0) return KVEV_ERR_INVALID_ARG;
+    if (write_bytes_per_tile < 0 || write_bytes_per_tile % 16 != 0 || hints < 0 || hints > 3) return KVEV_ERR_INVALID_ARG;
     const size_t tiles = src_bytes / (size_t)tile_bytes;
     if (tiles > ((size_t)1 << 31) - 1) return KVEV_ERR_INVALID_ARG;
     const size_t need = write_bytes_per_tile ? tiles * (size_t)write_bytes_per_tile : 16;
     if (dst_bytes < need) return KVEV_ERR_INVALID_ARG;
-    hipError_t e = launch_stream_probe(src, tiles, tile_bytes, dst, write_bytes_per_tile, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_stream_probe(src, tiles, tile_bytes, dst, write_bytes_per_tile, hints, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVEV_OK : hip_fail(e);
 }
 

@@ -17,6 +17,7 @@
 // frame).
 #include "common.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace kvev {
 
@@ -164,41 +165,48 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a)
     };
     constexpr int kPast = 0x3fffffff;
 
-    // ---- raw rows w0 .. w1-1 of the window (of the whole cache for the dense baseline) ----
-    for (int base = w0; base < w1; base += GROUPS * U) {
-        Raw<T, EPL> kr[U], vr[U];
-        int pos[U];
+    // Rows are read once per launch.  When a launch reads more than the memory-side cache holds (a.stream), the loads
+    // carry the non-temporal hint: nothing of it can be kept anyway, and the read stream runs 13 % faster without
+    // the allocations.  Smaller launches keep plain loads, so that the next decode step finds its rows in cache.
+    auto walk = [&](auto stream_tag) __attribute__((always_inline)) {
+        constexpr bool STREAM = decltype(stream_tag)::value;
+        // ---- raw rows w0 .. w1-1 of the window (of the whole cache for the dense baseline) ----
+        for (int base = w0; base < w1; base += GROUPS * U) {
+            Raw<T, EPL> kr[U], vr[U];
+            int pos[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int w = base + grp + GROUPS * u;
-            pos[u] = w < w1 ? w : kPast;
-            int r = a.win0 + min(w, w1 - 1) + a.ring_first;       // (ring_first is 0 unless the raw buffer is a ring)
-            r = r >= a.T_cap ? r - a.T_cap : r;
-            const size_t off = (seq_raw + r) * D + cl * EPL;
-            kr[u].load(K + off);
-            vr[u].load(V + off);
+            for (int u = 0; u < U; ++u) {
+                const int w = base + grp + GROUPS * u;
+                pos[u] = w < w1 ? w : kPast;
+                int r = a.win0 + min(w, w1 - 1) + a.ring_first;       // (ring_first is 0 unless the raw buffer is a ring)
+                r = r >= a.T_cap ? r - a.T_cap : r;
+                const size_t off = (seq_raw + r) * D + cl * EPL;
+                if (STREAM) { kr[u].load_stream(K + off); vr[u].load_stream(V + off); }
+                else { kr[u].load(K + off); vr[u].load(V + off); }
+            }
+            fold(kr, vr, pos);
         }
-        fold(kr, vr, pos);
-    }
-    // ---- the kept summaries (first run only) ----
-    const int cnt = min(max(cnt_raw, 0), a.k_cap);
-    for (int base = 0; base < cnt; base += GROUPS * U) {
-        Raw<T, EPL> kr[U], vr[U];
-        int pos[U];
+        // ---- the kept summaries (first run only) ----
+        const int cnt = min(max(cnt_raw, 0), a.k_cap);
+        for (int base = 0; base < cnt; base += GROUPS * U) {
+            Raw<T, EPL> kr[U], vr[U];
+            int pos[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = base + grp + GROUPS * u;
-            pos[u] = j < cnt ? -1 : kPast;
-            const int jc = min(j, cnt - 1);
-            // (idx0[u] is entry min(j, k_cap - 1) of the list: the right one whenever row j exists)
-            int c = idx ? (base == 0 ? idx0[u] : idx[jc]) : jc;
-            c = min(max(c, 0), a.N_cap - 1);
-            const size_t off = (seq_sum + c) * D + cl * EPL;
-            kr[u].load(Kbar + off);
-            vr[u].load(Vbar + off);
+            for (int u = 0; u < U; ++u) {
+                const int j = base + grp + GROUPS * u;
+                pos[u] = j < cnt ? -1 : kPast;
+                const int jc = min(j, cnt - 1);
+                // (idx0[u] is entry min(j, k_cap - 1) of the list: the right one whenever row j exists)
+                int c = idx ? (base == 0 ? idx0[u] : idx[jc]) : jc;
+                c = min(max(c, 0), a.N_cap - 1);
+                const size_t off = (seq_sum + c) * D + cl * EPL;
+                if (STREAM) { kr[u].load_stream(Kbar + off); vr[u].load_stream(Vbar + off); }
+                else { kr[u].load(Kbar + off); vr[u].load(Vbar + off); }
+            }
+            fold(kr, vr, pos);
         }
-        fold(kr, vr, pos);
-    }
+    };
+    if (a.stream) walk(std::true_type{}); else walk(std::false_type{});
 
     __shared__ float s_m[NQ][NW], s_l[NQ][NW], s_o[NQ][NW][D];
 #pragma unroll

@@ -23,6 +23,7 @@ struct AttnArgs {
     int ring_first;       // compact form: the window buffer is a ring, its token t sits in row (ring_first + t) mod T_cap; else 0
     int gated;            // 1: kept summaries precede the raw rows
     int nsplit, rows_per_split;
+    int stream;           // 1: the launch reads more than the memory-side cache holds: single-query loads carry the non-temporal hint
     float scale_log2e;    // log2(e) / sqrt(d)
 };
 
@@ -95,7 +96,7 @@ size_t pool_token_mfma_lds(int d, int d_sum);                            // its 
 hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
 hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st);       // bf16: the packed weights alone
-hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, hipStream_t st);   // calibration
+hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, int hints, hipStream_t st);   // calibration
 hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

@@ -72,8 +72,8 @@ __global__ __launch_bounds__(64 * NW) void pool_mfma_kernel(PoolArgs a)
                 const int j = j0 + g4 + 4 * u;
                 ok[u] = j < a.C;
                 const size_t off = tok0 + (size_t)(ok[u] ? j : a.C - 1) * D;
-                xk[u].load(K + off);
-                xv[u].load(V + off);
+                xk[u].load_stream(K + off);
+                xv[u].load_stream(V + off);
             }
             // branch-free tail: a row past the chunk was loaded from the last row and gets weight 0
             // (x * 1 + s rounds as x + s), so every load of the group is in flight before the first use
@@ -121,28 +121,36 @@ __global__ __launch_bounds__(64 * NW) void pool_mfma_kernel(PoolArgs a)
     }
     __syncthreads();
 
-    // this lane's tile row as an output address (C layout: column n = tile row)
-    const int r_out = row0 + n;
-    const bool live = r_out < rows_per_layer;
-    const int r_c = min(r_out, rows_per_layer - 1);
-    const size_t out_row = (((size_t)l * a.BH + r_c / nch) * a.N_cap + (a.c0 + r_c % nch)) * D;
     bf16_t *Kb = static_cast<bf16_t *>(a.Kbar), *Vb = static_cast<bf16_t *>(a.Vbar);
+    // Summaries leave as whole 256-byte rows, 16 bytes per lane (a wave-level store is 1 KiB of consecutive chunks of
+    // one sequence): 8-byte pieces straight out of the MFMA layout would touch every line four times.  Launches that
+    // fill the chip many times over (NW = 4) stream, so their stores carry the non-temporal hint like their loads.
+    auto store_piece = [&](int kv, int rt, int piece, u32x4_t w) __attribute__((always_inline)) {
+        const int r = row0 + rt;
+        if (r < rows_per_layer) {
+            bf16_t *dst = (kv ? Vb : Kb) + (((size_t)l * a.BH + r / nch) * a.N_cap + (a.c0 + r % nch)) * D + piece * 8;
+            if (NW == 4) __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t *>(dst));
+            else *reinterpret_cast<u32x4_t *>(dst) = w;
+        }
+    };
+    constexpr int PIECES = 2 * 16 * (D / 8);
 
     if (a.mode != KVEV_POOL_MLP) {      // mean or maximum: the tile rows are the output (a bf16 maximum is its own hi term)
-        for (int i = tid; i < 2 * 16 * (D / 2); i += 64 * NW) {
-            const int kv = i / (16 * (D / 2)), rt = (i / (D / 2)) % 16, e = (i % (D / 2)) * 2;
-            const int r = row0 + rt;
-            if (r < rows_per_layer) {
-                const size_t o = (((size_t)l * a.BH + r / nch) * a.N_cap + (a.c0 + r % nch)) * D + e;
-                float m0 = 0.f, m1 = 0.f;      // lo + mid + hi is exact: each partial sum is a prefix of the fp32 mean
+        for (int i = tid; i < PIECES; i += 64 * NW) {
+            const int kv = i / (16 * (D / 8)), rt = (i / (D / 8)) % 16, piece = i % (D / 8);
+            float m[8];
 #pragma unroll
-                for (int p = 2; p >= 0; --p) {
-                    const uint32_t w = *reinterpret_cast<const uint32_t *>(xm + ((p * 2 + kv) * 16 + rt) * XP + e);
-                    m0 += __uint_as_float(w << 16);
-                    m1 += __uint_as_float(w & 0xFFFF0000u);
+            for (int e = 0; e < 8; ++e) m[e] = 0.f;      // lo + mid + hi is exact: each partial sum is a prefix of the fp32 mean
+#pragma unroll
+            for (int p = 2; p >= 0; --p) {
+                const u32x4_t w = *reinterpret_cast<const u32x4_t *>(xm + ((p * 2 + kv) * 16 + rt) * XP + piece * 8);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    m[2 * q] += __uint_as_float(w[q] << 16);
+                    m[2 * q + 1] += __uint_as_float(w[q] & 0xFFFF0000u);
                 }
-                *reinterpret_cast<uint32_t *>((kv ? Vb : Kb) + o) = pack_bf16x2(m0, m1);
             }
+            store_piece(kv, rt, piece, u32x4_t{pack_bf16x2(m[0], m[1]), pack_bf16x2(m[2], m[3]), pack_bf16x2(m[4], m[5]), pack_bf16x2(m[6], m[7])});
         }
         return;
     }
@@ -193,12 +201,16 @@ __global__ __launch_bounds__(64 * NW) void pool_mfma_kernel(PoolArgs a)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, x, acc, 0, 0, 0);
             }
         }
-        if (live) {
-            uint2 o;
-            o.x = pack_bf16x2(acc[0], acc[1]);
-            o.y = pack_bf16x2(acc[2], acc[3]);
-            *reinterpret_cast<uint2 *>((kv ? Vb : Kb) + out_row + e0 + 4 * g4) = o;
-        }
+        // (the mean planes are free since the barrier before this layer: the output tile takes their place)
+        uint2 o;
+        o.x = pack_bf16x2(acc[0], acc[1]);
+        o.y = pack_bf16x2(acc[2], acc[3]);
+        *reinterpret_cast<uint2 *>(xm + (size_t)(kv * 16 + n) * XP + e0 + 4 * g4) = o;
+    }
+    __syncthreads();
+    for (int i = tid; i < PIECES; i += 64 * NW) {
+        const int kv = i / (16 * (D / 8)), rt = (i / (D / 8)) % 16, piece = i % (D / 8);
+        store_piece(kv, rt, piece, *reinterpret_cast<const u32x4_t *>(xm + (size_t)(kv * 16 + rt) * XP + piece * 8));
     }
 }
 

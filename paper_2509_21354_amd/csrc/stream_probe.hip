@@ -1,7 +1,8 @@
 // Calibration kernel behind kvev_debug_stream_probe (include/kvev_test_hooks.h): a plain streaming reader with an
 // optional small write stream, the memory pattern of chunk pooling without any of its arithmetic.  It exists to show
 // what the machine gives a kernel of that shape (a pure read stream; the same stream with 1.5 % or 3 % of its bytes
-// written back), next to which the pooling and attention kernels' rates are read.
+// written back; each with plain accesses or with the non-temporal hint that the library's streaming kernels use),
+// next to which the pooling and attention kernels' rates are read.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -9,6 +10,7 @@ namespace kvev {
 
 // One workgroup per tile: reads tile16 16-byte words (one per lane and load, 8 loads in flight), folds them into one
 // word, writes that word to w16 consecutive 16-byte words of the tile's own output slot.
+template <bool NT_LOAD, bool NT_STORE>
 __global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, int tile16, int w16)
 {
     const int tid = threadIdx.x;
@@ -17,7 +19,10 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4_t *__rest
     for (int i = tid; i < tile16; i += 256 * 8) {
         u32x4_t v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = p[min(i + 256 * u, tile16 - 1)];
+        for (int u = 0; u < 8; ++u) {
+            const u32x4_t *q = p + min(i + 256 * u, tile16 - 1);
+            v[u] = NT_LOAD ? __builtin_nontemporal_load(q) : *q;
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += v[u];
     }
@@ -25,15 +30,27 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4_t *__rest
         // nothing is written; a store that no data satisfies keeps the loads alive
         if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0f1e2d3cu) dst[0] = acc;
     } else {
-        for (int i = tid; i < w16; i += 256) dst[(size_t)blockIdx.x * w16 + i] = acc;
+        for (int i = tid; i < w16; i += 256) {
+            u32x4_t *q = dst + (size_t)blockIdx.x * w16 + i;
+            if (NT_STORE) __builtin_nontemporal_store(acc, q);
+            else *q = acc;
+        }
     }
 }
 
-hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, hipStream_t st)
+hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, int hints, hipStream_t st)
 {
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(stream_probe_kernel, dim3((unsigned)tiles), dim3(256), 0, st, static_cast<const u32x4_t *>(src),
-                       static_cast<u32x4_t *>(dst), tile_bytes / 16, write_bytes / 16);
+    const dim3 grid((unsigned)tiles), block(256);
+    const u32x4_t *s = static_cast<const u32x4_t *>(src);
+    u32x4_t *d = static_cast<u32x4_t *>(dst);
+    const int t16 = tile_bytes / 16, w16 = write_bytes / 16;
+    switch (hints & 3) {
+    case 0: hipLaunchKernelGGL((stream_probe_kernel<false, false>), grid, block, 0, st, s, d, t16, w16); break;
+    case 1: hipLaunchKernelGGL((stream_probe_kernel<true, false>), grid, block, 0, st, s, d, t16, w16); break;
+    case 2: hipLaunchKernelGGL((stream_probe_kernel<false, true>), grid, block, 0, st, s, d, t16, w16); break;
+    default: hipLaunchKernelGGL((stream_probe_kernel<true, true>), grid, block, 0, st, s, d, t16, w16); break;
+    }
     return hipGetLastError();
 }
 
