@@ -34,6 +34,8 @@ struct PoolArgs {
     int L, BH, d, T_cap, C, N_cap, d_sum;
     int c0, c1;
     int mode;
+    int compute_units;    // of the device the launch goes to
+    int flush_shift;      // the persistent form writes its summaries once per 2^flush_shift ticks of the 100 MHz real-time counter
 };
 
 struct LstmArgs {

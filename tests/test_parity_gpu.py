@@ -161,6 +161,10 @@ POOL_CASES = [
     _cfg(137, "bf16", d=64, T=200, C=40, d_sum=256, L=1, B=1, H=3),     # widest hidden layer the per-token kernel holds in LDS
     _cfg(138, "bf16", d=128, T=96, C=16, d_sum=256, L=1, B=1, H=2),     # ... and one it does not (generic kernel for that mode)
     _cfg(139, "bf16", d=128, T=200, C=48, d_sum=192, L=2, B=1, H=9),    # its widest at d = 128; 9 rows per layer: ragged tile
+    # 2048 and 2080 tiles: the persistent form of the matrix-core kernel (a workgroup walks several tiles and holds
+    # their summaries back until the next write slot), full and ragged
+    _cfg(129, "bf16", d=128, T=1026, C=2, d_sum=128, L=1, B=4, H=16),
+    _cfg(130, "bf16", d=64, T=2052, C=4, d_sum=64, L=1, B=5, H=13),
 ]
 
 
