@@ -630,7 +630,8 @@ def calibrate_stream(torch, kb):
     per 256 KiB tile, no arithmetic: kvev_debug_stream_probe) reads 17 GB with no writes, then with 1.5 % and 3 % of
     the bytes written back: what the machine gives the memory pattern of chunk pooling (which writes one summary row
     per chunk of 32 rows: 3 %); each with plain accesses and with the non-temporal hint on loads and stores (what the
-    library's streaming kernels use).  Beside them the library's own pure reader (dense decode attention), pooling in mean
+    library's streaming kernels use), and with the writes held back and issued in chip-wide bursts (what pooling does
+    at scale).  Beside them the library's own pure reader (dense decode attention), pooling in mean
     mode (the same read / write mix as the MLP mode, no matrix work) and a plain device copy."""
     from paper_2509_21354_amd import synth
     cfg = synth.CONFIGS[3]
@@ -651,8 +652,10 @@ def calibrate_stream(torch, kb):
     nbytes = kv["K"].numel() * 2
     tile = 256 << 10
     dst = torch.empty((nbytes // tile) * 8192 + 16, dtype=torch.uint8, device="cuda")
-    for hname, hints in (("plain", 0), ("nontemporal", 3)):
+    for hname, hints in (("plain", 0), ("nontemporal", 3), ("nontemporal_bursts", 7)):
         for name, wb in (("probe_pure_read", 0), ("probe_read_plus_1.5pct_write", 4096), ("probe_read_plus_3pct_write", 8192)):
+            if wb == 0 and hints & 4:
+                continue                  # (bursts are about the writes)
             t = t_of(lambda: kb.kvev_debug_stream_probe(kv["K"], tile, dst, wb, hints), 5)
             out[f"{name}_{hname}"] = {"bytes_read": nbytes, "bytes_written": (nbytes // tile) * wb, "us": round(t, 1),
                                       "read_GBps": round(nbytes / t / 1e3, 1),

@@ -37,8 +37,10 @@ int kvev_debug_lstm_fused_min_groups(int min_groups);
  * none) per tile to dst (device memory of at least tiles * write_bytes_per_tile
  * bytes, 16 at least).  The memory pattern of chunk pooling without its
  * arithmetic.  hints: bit 0 = the loads, bit 1 = the stores carry the
- * non-temporal hint (what the library's own streaming kernels use); 0 = plain
- * accesses.  Enqueued on `stream`; errors: INVALID_ARG. */
+ * non-temporal hint (what the library's own streaming kernels use); bit 2 =
+ * persistent workgroups hold their outputs back and write them in chip-wide
+ * bursts, once per 82 us slot of the real-time counter (what chunk pooling does
+ * at scale; write_bytes_per_tile at most 48 KiB then); 0 = plain accesses.  Enqueued on `stream`; errors: INVALID_ARG. */
 int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, void *dst, size_t dst_bytes,
                             int write_bytes_per_tile, int hints, void *stream);
 

@@ -516,7 +516,8 @@ int kvev_debug_stream_probe(const void *src, size_t src_bytes, int tile_bytes, v
 {
     if (!src || !dst || !aligned16(src) || !aligned16(dst)) return KVEV_ERR_INVALID_ARG;
     if (tile_bytes < 4096 || tile_bytes % 4096 != 0 || src_bytes % (size_t)tile_bytes != 0) return KVEV_ERR_INVALID_ARG;
-    if (write_bytes_per_tile < 0 || write_bytes_per_tile % 16 != 0 || hints < 0 || hints > 3) return KVEV_ERR_INVALID_ARG;
+    if (write_bytes_per_tile < 0 || write_bytes_per_tile % 16 != 0 || hints < 0 || hints > 7) return KVEV_ERR_INVALID_ARG;
+    if ((hints & 4) && write_bytes_per_tile > 48 * 1024) return KVEV_ERR_INVALID_ARG;
     const size_t tiles = src_bytes / (size_t)tile_bytes;
     if (tiles > ((size_t)1 << 31) - 1) return KVEV_ERR_INVALID_ARG;
     const size_t need = write_bytes_per_tile ? tiles * (size_t)write_bytes_per_tile : 16;
