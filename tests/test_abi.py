@@ -54,6 +54,25 @@ def test_debug_pair_wait_validation():
 FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
 
 
+def test_stream_probe_validation():
+    """The calibration hook checks its arguments on the host before any launch."""
+    L = kb.lib()
+    f = L.kvev_debug_stream_probe
+    ok_args = dict(src=FAKE, src_bytes=1 << 20, tile=4096, dst=FAKE, dst_bytes=1 << 20, wb=16, hints=0)
+
+    def call(**kw):
+        a = dict(ok_args, **kw)
+        return f(a["src"], a["src_bytes"], a["tile"], a["dst"], a["dst_bytes"], a["wb"], a["hints"], None)
+    assert call(src=None) == kb.ERR_INVALID_ARG
+    assert call(dst=ctypes.c_void_p(0x1008)) == kb.ERR_INVALID_ARG              # not 16-byte aligned
+    assert call(tile=4000) == kb.ERR_INVALID_ARG                                # not a multiple of 4096
+    assert call(src_bytes=(1 << 20) + 4096, tile=8192) == kb.ERR_INVALID_ARG    # the tile does not divide the source
+    assert call(wb=24) == kb.ERR_INVALID_ARG                                    # not a multiple of 16
+    assert call(wb=8192, dst_bytes=4096) == kb.ERR_INVALID_ARG                  # 256 tiles x 8 KiB do not fit
+    assert call(hints=8) == kb.ERR_INVALID_ARG and call(hints=-1) == kb.ERR_INVALID_ARG
+    assert call(hints=4, wb=64 * 1024, dst_bytes=1 << 30) == kb.ERR_INVALID_ARG  # bursts hold at most 48 KiB per tile
+
+
 def _shape(**kw):
     return kb.make_shape(synth.CONFIGS[2], **kw)
 
