@@ -30,6 +30,14 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member);
  * default.  Errors: INVALID_ARG for a negative value. */
 int kvev_debug_lstm_fused_min_groups(int min_groups);
 
+/* The single-query attention kernels read their rows with the non-temporal hint
+ * when a launch reads more than `bytes` (default 256 MiB, what the memory-side
+ * cache holds; 0 restores the default).  Lowering it to 1 lets a parity test run
+ * the streaming form of the loads on a shape the CPU oracle finishes in seconds;
+ * the hint changes how the caches treat the rows, never the result.  Errors:
+ * none (always KVEV_OK). */
+int kvev_debug_attn_stream_bytes(size_t bytes);
+
 /* Calibration of the memory system for the benchmark's roofline notes (bench.py
  * --calibrate-stream): a plain streaming kernel, one workgroup per tile, reads
  * src_bytes of device memory in tiles of tile_bytes (a multiple of 4096 that

@@ -29,7 +29,8 @@ OP_LSTM_PREPARE, OP_LSTM_GATE_PREPARED = 6, 7
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_lstm_prepare", "kvev_lstm_gate_prepared", "kvev_select", "kvev_gated_attention",
            "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
            "kvev_status_string", "kvev_last_hip_error", "kvev_version")
-TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups", "kvev_debug_stream_probe")      # include/kvev_test_hooks.h
+TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups", "kvev_debug_stream_probe",
+              "kvev_debug_attn_stream_bytes")      # include/kvev_test_hooks.h
 
 
 class Shape(ctypes.Structure):
@@ -80,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_workspace_bytes.restype = sz
         L.kvev_debug_pair_wait.argtypes = [ci, ci]
         L.kvev_debug_pair_wait.restype = ci
+        L.kvev_debug_attn_stream_bytes.argtypes = [sz]
+        L.kvev_debug_attn_stream_bytes.restype = ci
         L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
         L.kvev_debug_lstm_fused_min_groups.restype = ci
         L.kvev_debug_stream_probe.argtypes = [vp, sz, ci, vp, sz, ci, ci, vp]
@@ -138,6 +141,10 @@ def make_shape(cfg=None, **kw) -> Shape:
 
 def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> None:
     _check(lib().kvev_debug_pair_wait(spin_limit, mute_member), "kvev_debug_pair_wait")
+
+
+def kvev_debug_attn_stream_bytes(nbytes: int = 0) -> None:
+    _check(lib().kvev_debug_attn_stream_bytes(nbytes), "kvev_debug_attn_stream_bytes")
 
 
 def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:

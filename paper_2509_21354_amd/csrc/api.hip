@@ -95,7 +95,8 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 }
 
 // a frame of queries per key-value sequence (all heads of a group count) goes to the matrix cores
-constexpr size_t kStreamBytes = (size_t)256 << 20;     // what the memory-side cache holds
+constexpr size_t kStreamBytesDefault = (size_t)256 << 20;     // what the memory-side cache holds
+static std::atomic<size_t> g_stream_bytes{kStreamBytesDefault};
 static bool attn_takes_mq(const kvev_shape *sh, int Tq)
 {
     return sh->dtype == KVEV_BF16 && (int64_t)(sh->H / kv_heads(sh)) * Tq >= 16;
@@ -188,7 +189,7 @@ static int attention_common(const kvev_shape *sh, const void *Q, int Tq, const v
     a.win0 = win0; a.ring_first = ring_first; a.gated = gated ? 1 : 0;
     a.nsplit = p.nsplit; a.rows_per_split = p.rows_per_split;
     // rows that no cache can hold until the next call are read with the streaming hint (256 MB: the memory-side cache)
-    a.stream = (size_t)a.S * (size_t)n_rows * sh->d * 2 * (sh->dtype == KVEV_F32 ? 4 : 2) > kStreamBytes ? 1 : 0;
+    a.stream = (size_t)a.S * (size_t)n_rows * sh->d * 2 * (sh->dtype == KVEV_F32 ? 4 : 2) > g_stream_bytes.load(std::memory_order_relaxed) ? 1 : 0;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)sh->d));
     hipError_t e = mq ? launch_attn_mq(a, static_cast<hipStream_t>(stream))
                       : launch_attn_decode(a, sh->dtype, static_cast<hipStream_t>(stream));
@@ -501,6 +502,12 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member)
     if (spin_limit < 1 || mute_member < -1 || mute_member > 1) return KVEV_ERR_INVALID_ARG;
     g_pair_spin_limit = spin_limit;
     g_pair_mute = mute_member;
+    return KVEV_OK;
+}
+
+int kvev_debug_attn_stream_bytes(size_t bytes)
+{
+    g_stream_bytes = bytes == 0 ? kStreamBytesDefault : bytes;
     return KVEV_OK;
 }
 

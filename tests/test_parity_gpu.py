@@ -93,6 +93,43 @@ def test_gated_attention_teacher_forced(cfg):
     assert_close_storage(O, ref, cfg.dtype, "gated O")
 
 
+@pytest.mark.parametrize("cfg", [c for c in GATED_CASES if c.Tq < 16], ids=lambda c: c.name)
+def test_streaming_loads_change_no_bit(cfg):
+    """Large launches read their rows with the non-temporal hint (a launch above 256 MiB; here forced by the test hook).
+    The hint tells the caches how to treat the rows: the results, gated and dense, fp32 and bf16, stay bit for bit."""
+    T_cap = cfg.T + 7
+    N_cap = T_cap // cfg.C
+    t = synth.make_qkv(cfg, "cpu", T_cap=T_cap)
+    g_ = torch.Generator().manual_seed(cfg.number)
+    lead = (cfg.L, cfg.B, cfg.H)
+    Kbar = torch.randn(lead + (N_cap, cfg.d), generator=g_).to(cfg.torch_dtype).cuda()
+    Vbar = torch.randn(lead + (N_cap, cfg.d), generator=g_).to(cfg.torch_dtype).cuda()
+    util = torch.randn(lead + (N_cap,), generator=g_)
+    k_cap = max(1, min(cfg.k, N_cap) + 2)
+    idx, count = orc.select_topk(util, cfg.T, cfg.C, cfg.W, cfg.k, k_cap)
+    idx, count = torch.from_numpy(idx).cuda(), torch.from_numpy(count).cuda()
+    g = dev(t)
+    sh = kb.make_shape(cfg, T_cap=T_cap, N_cap=N_cap)
+    ws = kb.alloc_workspace(max(kb.workspace_bytes(kb.OP_GATED_ATTENTION, sh, cfg.Tq, k_cap),
+                                kb.workspace_bytes(kb.OP_DENSE_ATTENTION, sh, cfg.Tq)))
+    outs = []
+    try:
+        for nbytes in (0, 1):            # the default rule (these shapes: plain loads), then every launch streams
+            kb.kvev_debug_attn_stream_bytes(nbytes)
+            Og, Od = torch.full_like(g["Q"], 7.0), torch.full_like(g["Q"], 7.0)
+            kb.kvev_gated_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], Kbar, Vbar, idx, count, k_cap, Og, ws)
+            kb.kvev_dense_attention(sh, g["Q"], cfg.Tq, g["K"], g["V"], Od, ws)
+            torch.cuda.synchronize()
+            outs.append((Og, Od))
+    finally:
+        kb.kvev_debug_attn_stream_bytes(0)
+    assert torch.equal(outs[0][0].view(torch.uint8), outs[1][0].view(torch.uint8))
+    assert torch.equal(outs[0][1].view(torch.uint8), outs[1][1].view(torch.uint8))
+    ref = orc.gated_attention(t["Q"], t["K"], t["V"], Kbar.cpu(), Vbar.cpu(), idx.cpu().numpy(), count.cpu().numpy(),
+                              cfg.T, cfg.C, cfg.W)
+    assert_close_storage(outs[1][0], ref, cfg.dtype, "gated O, streaming loads")
+
+
 def test_attention_empty_cases():
     cfg = _cfg(129, "f32", T=0)
     t = synth.make_qkv(cfg, "cpu", T_cap=16)
