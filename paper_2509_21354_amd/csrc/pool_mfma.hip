@@ -19,6 +19,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include <algorithm>
+#include <atomic>
 
 namespace kvev {
 
@@ -287,11 +288,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(Poo
     flush();
 }
 
-// Workgroups of the persistent form: as many as stay resident at once (by LDS and registers), per compute unit.
+// Workgroups of the persistent form: as many as stay resident at once (by LDS and registers), per compute unit.  The
+// answer for the last LDS size asked about is kept (one word: size and answer together), so that a serving loop does not
+// query the runtime on every launch.
 template <int D> static int persistent_grid(size_t lds, int compute_units)
 {
+    static std::atomic<uint64_t> last{0};
+    const uint64_t seen = last.load(std::memory_order_relaxed);
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pool_mfma_kernel<D, 4>, 256, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (seen != 0 && (seen >> 8) == lds) per_cu = (int)(seen & 0xff);
+    else {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pool_mfma_kernel<D, 4>, 256, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+        per_cu = std::min(per_cu, 255);
+        last.store(((uint64_t)lds << 8) | (uint64_t)per_cu, std::memory_order_relaxed);
+    }
     return per_cu * compute_units;
 }
 
