@@ -92,8 +92,10 @@ typedef struct { const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s; } kvev_lstm_
  *   K, V        [L,B,H,T_cap,d]   read: tokens [chunk_begin*C, chunk_end*C)
  *   Kbar, Vbar  [L,B,H,N_cap,d]   written: rows [chunk_begin, chunk_end) only
  * Needs 0 <= chunk_begin <= chunk_end <= floor(T/C) <= N_cap.  Workspace: none
- * (ws may be NULL).  Errors: INVALID_ARG for null/misaligned pointers or a bad
- * range; UNSUPPORTED for d, dtype or pool_mode outside the lists above. */
+ * (ws may be NULL).  Errors: INVALID_ARG for null/misaligned pointers, a bad
+ * range, more than 2^30 (sequence, chunk) pairs in one call or more than
+ * 2^31 - 1 summary rows in Kbar; UNSUPPORTED for d, dtype or pool_mode outside
+ * the lists above. */
 int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int pool_mode,
                     const kvev_mlp_w *wK, const kvev_mlp_w *wV, int chunk_begin, int chunk_end,
                     void *Kbar, void *Vbar, void *ws, size_t ws_bytes, void *stream);

@@ -1,6 +1,7 @@
 // C-ABI layer: argument validation (host only, before any HIP call), launch
 // planning (split counts, workspace carving) and dispatch to the kernels.
 #include <math.h>
+#include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -295,6 +296,8 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     }
     if (chunk_begin == chunk_end) return KVEV_OK;
     if ((int64_t)sh->L * sh->B * kv_heads(sh) * (chunk_end - chunk_begin) > (int64_t)1 << 30) return KVEV_ERR_INVALID_ARG;
+    // (summary rows are indexed with 32 bits in the kernels)
+    if ((int64_t)sh->L * sh->B * kv_heads(sh) * sh->N_cap > (int64_t)INT32_MAX) return KVEV_ERR_INVALID_ARG;
 
     PoolArgs a;
     memset(&a, 0, sizeof a);
