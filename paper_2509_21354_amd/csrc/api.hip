@@ -95,9 +95,11 @@ static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
     return p;
 }
 
-// a frame of queries per key-value sequence (all heads of a group count) goes to the matrix cores
+// single-query launches that read more than this take their rows with the non-temporal hint
 constexpr size_t kStreamBytesDefault = (size_t)256 << 20;     // what the memory-side cache holds
 static std::atomic<size_t> g_stream_bytes{kStreamBytesDefault};
+
+// a frame of queries per key-value sequence (all heads of a group count) goes to the matrix cores
 static bool attn_takes_mq(const kvev_shape *sh, int Tq)
 {
     return sh->dtype == KVEV_BF16 && (int64_t)(sh->H / kv_heads(sh)) * Tq >= 16;
