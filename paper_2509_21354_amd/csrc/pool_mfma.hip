@@ -20,6 +20,7 @@
 #include "kernels.hpp"
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 namespace kvev {
 
@@ -132,49 +133,85 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(Poo
     };
     static_assert(NS == 2, "emit() picks the first free of two slots");
 
+    // One batch = 32 tokens of a tile row (16 loads of 16 bytes per lane: 8 tokens x {K, V}).
+    // first element this lane reads of row i (of this wave) of a tile
+    auto row_base = [&](int tl, int i) __attribute__((always_inline)) {
+        const int r = min((tl % tiles_per_layer) * 16 + wave * RPW + i, rows_per_layer - 1);   // clamped: a tail row repeats the last one
+        const size_t s = (size_t)(tl / tiles_per_layer) * a.BH + r / nch;
+        const int c = a.c0 + r % nch;
+        return (s * a.T_cap + (size_t)c * a.C) * D + n * EPL;
+    };
+    Raw<bf16_t, EPL> xk[8], xv[8];
+    // tokens j0 + g4 + 4u, u in [U0, U1): branch-free tail, a token past the chunk is loaded from the last one and gets
+    // weight 0 (x * 1 + s rounds as x + s; the maximum needs no weight: the repeated token changes nothing), so every
+    // load of a batch is in flight before the first use
+    auto issue = [&](size_t tok0, int j0, auto u0_tag, auto u1_tag) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = decltype(u0_tag)::value; u < decltype(u1_tag)::value; ++u) {
+            const int j = j0 + g4 + 4 * u;
+            const size_t off = tok0 + (size_t)(j < a.C ? j : a.C - 1) * D;
+            xk[u].load_stream(K + off);
+            xv[u].load_stream(V + off);
+        }
+    };
+    float sk[EPL], sv[EPL];
+    auto consume = [&](int j0, auto u0_tag, auto u1_tag) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = decltype(u0_tag)::value; u < decltype(u1_tag)::value; ++u) {
+            const float wgt = j0 + g4 + 4 * u < a.C ? 1.f : 0.f;
+            float fk[EPL], fv[EPL];
+            xk[u].get(fk);
+            xv[u].get(fv);
+            if (is_max) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) { sk[e] = fmaxf(sk[e], fk[e]); sv[e] = fmaxf(sv[e], fv[e]); }
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) { sk[e] = fmaf(fk[e], wgt, sk[e]); sv[e] = fmaf(fv[e], wgt, sv[e]); }
+            }
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I4 = std::integral_constant<int, 4>;
+    using I8 = std::integral_constant<int, 8>;
+
     int tile = blockIdx.x;           // (one tile per workgroup unless the form is persistent)
+    // The persistent form keeps half a batch ahead of itself at all times: the first 4 tokens of the next batch are
+    // requested before the last 4 of this one are used, across rows, tiles and the MLP phase, so that a workgroup has
+    // loads in flight while its waves are at the barriers and in the matrix work.
+    size_t tok0 = row_base(tile, 0);
+    if constexpr (STAGED) issue(tok0, 0, I0{}, I4{});
     do {
         const int l = tile / tiles_per_layer;
-        const int row0 = (tile % tiles_per_layer) * 16;
 
         // ---- 1. stream the chunks, fp32 means to LDS ------------------------------
         for (int i = 0; i < RPW; ++i) {
-            flush_if_new_slot();                                 // (between rows: no loaded row is waiting in registers)
             const int rt = wave * RPW + i;                       // row within the tile
-            const int r = min(row0 + rt, rows_per_layer - 1);    // clamped: a tail row repeats the last one
-            const size_t s = (size_t)l * a.BH + r / nch;
-            const int c = a.c0 + r % nch;
-            const size_t tok0 = (s * a.T_cap + (size_t)c * a.C) * D + n * EPL;
-            float sk[EPL], sv[EPL];
+            if constexpr (!STAGED) tok0 = row_base(tile, i);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) sk[e] = sv[e] = is_max ? -INFINITY : 0.f;
             for (int j0 = 0; j0 < a.C; j0 += 32) {
-                Raw<bf16_t, EPL> xk[8], xv[8];
-                bool ok[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int j = j0 + g4 + 4 * u;
-                    ok[u] = j < a.C;
-                    const size_t off = tok0 + (size_t)(ok[u] ? j : a.C - 1) * D;
-                    xk[u].load_stream(K + off);
-                    xv[u].load_stream(V + off);
-                }
-                // branch-free tail: a row past the chunk was loaded from the last row and gets weight 0
-                // (x * 1 + s rounds as x + s), so every load of the group is in flight before the first use
-                // (the maximum needs no weight: the repeated last row changes nothing)
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const float wgt = ok[u] ? 1.f : 0.f;
-                    float fk[EPL], fv[EPL];
-                    xk[u].get(fk);
-                    xv[u].get(fv);
-                    if (is_max) {
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) { sk[e] = fmaxf(sk[e], fk[e]); sv[e] = fmaxf(sv[e], fv[e]); }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) { sk[e] = fmaf(fk[e], wgt, sk[e]); sv[e] = fmaf(fv[e], wgt, sv[e]); }
+                if constexpr (STAGED) {
+                    flush_if_new_slot();
+                    issue(tok0, j0, I4{}, I8{});
+                    consume(j0, I0{}, I4{});
+                    // the batch after this one: same row, next row, first row of the next tile; after the last batch of
+                    // all, this one again (its values are never used)
+                    int jn = j0 + 32, in = i, tn = tile;
+                    if (jn >= a.C) {
+                        jn = 0; in = i + 1;
+                        if (in == RPW) {
+                            in = 0; tn = tile + (int)gridDim.x;
+                            if (tn >= ntiles) { tn = tile; in = i; jn = j0; }
+                        }
                     }
+                    const size_t tok0n = row_base(tn, in);
+                    issue(tok0n, jn, I0{}, I4{});
+                    consume(j0, I4{}, I8{});
+                    tok0 = tok0n;
+                } else {
+                    issue(tok0, j0, I0{}, I8{});
+                    consume(j0, I0{}, I8{});
                 }
             }
             const float cf = is_max ? 1.f : (float)a.C;
