@@ -6,7 +6,7 @@
 // of cache read, which puts it near the machine's ridge: the cache must still be
 // read only once per sequence, and the contractions must run on MFMA.
 //
-// A workgroup owns 64*QS queries of one sequence (16*QS per wave) and walks the
+// A workgroup owns 16*QS queries per wave (4 waves, or 8 for frames above 128 queries) of one sequence and walks the
 // rows in tiles of 64.  A tile's K and V rows are copied once, coalesced, into
 // LDS (a kept summary is reached through its chunk index); the copy of tile t+1
 // is in flight in registers while tile t is computed.  Both products are taken
@@ -32,15 +32,15 @@ constexpr float kNegBigMq = -1.0e30f;
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 typedef v4i16_t __attribute__((address_space(3))) lds_v4i16_t;
 
-template <int D, int QS>
-__global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles, int nblocks)
+template <int D, int QS, int NWV = 4>
+__global__ __launch_bounds__(64 * NWV, NWV == 4 ? 2 : 1) void attn_mq_kernel(AttnArgs a, int qtiles, int nblocks)
 {
-    constexpr int BN = 64, RP = D + 8, KS = D / 32, DT = D / 16, BM = 64 * QS;
+    constexpr int BN = 64, RP = D + 8, KS = D / 32, DT = D / 16, BM = 16 * NWV * QS, NT = 64 * NWV;
     // V rows are padded by 32 bytes: the transposing load has 16 lanes read 8 bytes each from 4 consecutive
     // rows, and a row pitch of 8 banks (mod 64) puts those 16 pieces in 16 different bank pairs; the 16-byte
     // row reads of K want the 16-byte padding instead
     constexpr int RPV = D + 16;
-    constexpr int CPT = BN * (D / 8) / 256;          // 16-byte chunks per thread per tile, for K and for V
+    constexpr int CPT = BN * (D / 8) / NT;          // 16-byte chunks per thread per tile, for K and for V
     __shared__ __align__(16) bf16_t s_k[BN * RP];    // row-major, padded rows
     __shared__ __align__(16) bf16_t s_v[BN * RPV];
 
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
 
     // staging role of this thread: column chunk dc of rows sr, sr + 256/(D/8), ...
     const int dc = tid % (D / 8), sr = tid / (D / 8);
-    constexpr int RSTEP = 256 / (D / 8);
+    constexpr int RSTEP = NT / (D / 8);
     u32x4_t kreg[CPT], vreg[CPT];
     // branch-free so that the copies stay in registers while the tile before is computed
 #define KVEV_MQ_FETCH(J0)                                                                              \
@@ -235,21 +235,24 @@ __global__ __launch_bounds__(256, 2) void attn_mq_kernel(AttnArgs a, int qtiles,
 #undef KVEV_MQ_FETCH_RAW
 #undef KVEV_MQ_FETCH_ANY
 
-template <int D, int QS>
+template <int D, int QS, int NWV = 4>
 static hipError_t launch_mq_t(const AttnArgs &a, hipStream_t st)
 {
-    const int qtiles = (a.G * a.Tq + 64 * QS - 1) / (64 * QS);
+    const int qtiles = (a.G * a.Tq + 16 * NWV * QS - 1) / (16 * NWV * QS);
     const size_t blocks = (size_t)a.S * qtiles;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_mq_kernel<D, QS>), dim3((unsigned)blocks), dim3(256), 0, st, a, qtiles, (int)blocks);
+    hipLaunchKernelGGL((attn_mq_kernel<D, QS, NWV>), dim3((unsigned)blocks), dim3(64 * NWV), 0, st, a, qtiles, (int)blocks);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_mq(const AttnArgs &a, hipStream_t st)
 {
     // 128 queries per workgroup halve the LDS traffic per flop; frames shorter than
-    // that would leave half the waves idle
+    // that would leave half the waves idle.  Frames of more than 128 queries take workgroups of 8 waves (256 queries):
+    // a tile of K and V is then fetched and staged once for all of them, instead of by two workgroups that meet in L2
+    // (dense launch at 256 queries and 32768 rows: 11.0 -> 10.0 ms; 10 tiles per workgroup: 290 -> 287 us).
     const bool wide = a.G * a.Tq > 64;
+    if (a.G * a.Tq > 128) return a.d == 64 ? launch_mq_t<64, 2, 8>(a, st) : launch_mq_t<128, 2, 8>(a, st);
     if (a.d == 64) return wide ? launch_mq_t<64, 2>(a, st) : launch_mq_t<64, 1>(a, st);
     return wide ? launch_mq_t<128, 2>(a, st) : launch_mq_t<128, 1>(a, st);
 }

@@ -32,6 +32,10 @@ CASES = [
     (_cfg(208, "bf16", d=128, H=2, H_kv=0, Tq=48, T=1100, C=32, W=130, k=8, L=1), 1),   # causal on the matrix cores
     (_cfg(209, "bf16", d=128, H=8, H_kv=2, Tq=16, T=1000, C=32, W=96, k=8, L=1), 1),   # causal + grouped, matrix cores
     (_cfg(210, "f32", d=128, H=6, H_kv=3, Tq=2, T=300, C=8, W=30, k=5), 1),        # causal + grouped, decode
+    # more than 128 queries per key-value sequence: workgroups of 8 waves (256 queries), last waves partly or wholly idle
+    (_cfg(211, "bf16", d=128, H=2, H_kv=0, Tq=150, T=1100, C=32, W=200, k=9, L=1, B=1), 0),
+    (_cfg(212, "bf16", d=64, H=8, H_kv=2, Tq=40, T=700, C=16, W=90, k=6, L=1, B=1), 1),      # 160, causal + grouped
+    (_cfg(213, "bf16", d=128, H=2, H_kv=0, Tq=300, T=900, C=32, W=320, k=7, L=1, B=1), 1),   # 300: two tiles, the second ragged
 ]
 
 

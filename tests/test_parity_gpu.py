@@ -67,6 +67,8 @@ GATED_CASES = [
     _cfg(117, "bf16", d=128, T=2048, C=32, W=256, k=19, Tq=70, L=1, B=2, H=2),   # matrix-core path, gather + window
     _cfg(118, "bf16", d=64, T=700, C=16, W=50, k=300, Tq=16, L=1, B=1, H=3),     # k > N_cand, ragged window
     _cfg(119, "bf16", d=128, T=100, C=32, W=256, k=4, Tq=33, L=1, B=1, H=2),     # no candidate: raw tokens only
+    _cfg(120, "bf16", d=128, T=1500, C=32, W=192, k=21, Tq=200, L=1, B=1, H=3),  # 8-wave workgroups (more than 128 queries)
+    _cfg(121, "bf16", d=64, T=800, C=16, W=70, k=11, Tq=257, L=1, B=1, H=2),     # ... two of them, the second with one query
 ]
 
 
