@@ -66,8 +66,14 @@ static int env_int(const char *name, int dflt)
 // with more, four 4-wave workgroups per compute unit and runs of at least 512 rows.
 static const int g_attn_target_blocks = env_int("KVEV_ATTN_TARGET_BLOCKS", -1);
 static const int g_attn_min_rows = env_int("KVEV_ATTN_MIN_ROWS", -1);
-// large pooling launches write their summaries once per 2^shift ticks of the 100 MHz real-time counter (8192 ticks = 82 us)
-static const int g_pool_flush_shift = std::min(std::max(env_int("KVEV_POOL_FLUSH_SHIFT", 13), 6), 40);
+// large pooling launches write their summaries once per 2^shift ticks of the 100 MHz real-time counter: 8192 ticks
+// (82 us) with the MLP, 4096 without (tiles complete faster; a slot should not outlast the two tiles a thread holds back)
+static const int g_pool_flush_shift_env = env_int("KVEV_POOL_FLUSH_SHIFT", -1);
+static int pool_flush_shift(int pool_mode)
+{
+    if (g_pool_flush_shift_env >= 0) return std::min(std::max(g_pool_flush_shift_env, 6), 40);
+    return pool_mode == KVEV_POOL_MLP ? 13 : 12;
+}
 
 static AttnPlan plan_attn(const kvev_shape *sh, int Tq, int n_rows)
 {
@@ -310,7 +316,7 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     }
     a.L = sh->L; a.BH = sh->B * kv_heads(sh); a.d = sh->d; a.T_cap = sh->T_cap; a.C = sh->C; a.N_cap = sh->N_cap;
     a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
-    a.compute_units = device_compute_units(); a.flush_shift = g_pool_flush_shift;
+    a.compute_units = device_compute_units(); a.flush_shift = pool_flush_shift(pool_mode);
     // bf16 storage with a hidden width the 16x16x32 tiling divides goes to the matrix cores
     const bool mfma = sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
     hipError_t e;
