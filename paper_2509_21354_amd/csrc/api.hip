@@ -261,9 +261,15 @@ static size_t lstm_ws_weights(const kvev_shape *sh)
 // The gate's scratch: a 256-byte head (its first word is the status word), the packed weights unless the caller
 // keeps them (kvev_lstm_prepare), the exchange slots of the paired recurrence where it applies, then the projections.
 constexpr size_t kLstmWsHead = 256;
+// KVEV_LSTM_QUAD=0 (read once) keeps d_g = 512 on pairs of workgroups where quadruples would be taken.
+static const int g_lstm_quad = env_int("KVEV_LSTM_QUAD", 1);
+static int lstm_split_of(const kvev_shape *sh)
+{
+    return lstm_takes_fused(sh) ? 0 : lstm_split(sh->d_g, sh->L, sh->B * kv_heads(sh), device_compute_units(), g_lstm_quad != 0);
+}
 static size_t lstm_exch_bytes(const kvev_shape *sh)
 {
-    return lstm_takes_fused(sh) ? 0 : lstm_pair_exch_bytes(sh->d_g, lstm_groups(sh), device_compute_units());
+    return lstm_split_exch_bytes(lstm_split_of(sh), sh->d_g, sh->L, sh->B * kv_heads(sh));
 }
 static size_t lstm_ws_pack(const kvev_shape *sh, bool prepared)
 {
@@ -390,6 +396,7 @@ static int lstm_gate_common(const kvev_shape *sh, const void *Kbar, const void *
             lstm_packed_pointers(sh, p, a);
             p += lstm_ws_weights(sh);
         }
+        a.split = lstm_split_of(sh);
         a.exch_bytes = lstm_exch_bytes(sh);
         a.exch = a.exch_bytes ? p : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);

@@ -46,8 +46,9 @@ struct LstmArgs {
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *whh_packed;   // workspace: W_hh in fragment order (16-byte pieces; fp16 inside)
     uint32_t *whh_max_bits;   // workspace: 32 partial maxima of |W_hh| per layer as bit patterns (their maximum fixes the power-of-two scale)
     const __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 *wih_packed;   // workspace: W_ih in fragment order
-    unsigned char *exch;  // workspace: exchange slots of the paired recurrence (lstm_pair_exch_bytes), or null
+    unsigned char *exch;  // workspace: exchange slots of the split recurrence (lstm_split_exch_bytes), or null
     size_t exch_bytes;    // 0: one workgroup per sequence group
+    int split;            // workgroups that share a sequence group in the recurrence: 0 (one), 2 or 4 (lstm_split)
     int pair_spin_limit;  // polls a wave of the paired recurrence spends on one wait before it gives up
     int pair_mute;        // member (0, 1) whose publications are withheld, -1: none (failure-path tests only)
     int32_t *status;      // workspace: word that a launch sets to 1 when a bounded wait expired (never cleared by the library)
@@ -58,15 +59,27 @@ struct LstmArgs {
     int fused;            // 1: the single-kernel form (d_g = 256, 32 sequences per workgroup, no projections in scratch)
 };
 
-// The recurrence runs a sequence group on a pair of workgroups that exchange h every step when the launch has at most
-// one workgroup per two compute units at d_g = 256, per compute unit at d_g = 512 (where a single workgroup is bound
-// by the weight stream out of L2 and a pair halves it): then all of them can be resident together on an idle
-// device (bounded waits in the kernel cover the rest).  The exchange needs 64 KiB of scratch per group and 256
-// hidden units.  0: not paired.
-inline size_t lstm_pair_exch_bytes(int d_g, long long groups, int compute_units)
+// How the two-kernel gate spreads a group of sequences over workgroups that exchange h every step (0: one workgroup
+// per 16 sequences, no exchange).  Pairs: 16 sequences on two workgroups when the launch has at most one workgroup
+// per two compute units at d_g = 256, per compute unit at d_g = 512 (where a single workgroup is bound by the weight
+// stream out of L2 and a pair halves it).  Quadruples: at d_g = 512, 32 sequences on four workgroups (a quarter of
+// the stream each, and every fragment serves two blocks of sequences) when that is at most one workgroup per
+// compute unit and a layer has more than 16 sequences.  Then all workgroups can be resident together on an idle
+// device (bounded waits in the kernels cover the rest).
+constexpr size_t kLstmPairExchBytes256 = 65536;     // scratch per group of 16 sequences and 256 hidden units
+constexpr size_t kLstmQuadExchBytes = 262144;       // scratch per group of 32 sequences
+inline int lstm_split(int d_g, int L, int BH, int compute_units, bool quad_allowed)
 {
-    if (d_g == 256 && 4 * groups <= compute_units) return (size_t)groups * 65536;
-    if (d_g == 512 && 2 * groups <= compute_units) return (size_t)groups * 131072;
+    const long long g16 = (long long)L * ((BH + 15) / 16), g32 = (long long)L * ((BH + 31) / 32);
+    if (d_g == 512 && quad_allowed && BH > 16 && 4 * g32 <= compute_units) return 4;
+    if (d_g == 256 && 4 * g16 <= compute_units) return 2;
+    if (d_g == 512 && 2 * g16 <= compute_units) return 2;
+    return 0;
+}
+inline size_t lstm_split_exch_bytes(int split, int d_g, int L, int BH)
+{
+    if (split == 4) return (size_t)L * ((BH + 31) / 32) * kLstmQuadExchBytes;
+    if (split == 2) return (size_t)L * ((BH + 15) / 16) * (d_g / 256) * kLstmPairExchBytes256;
     return 0;
 }
 
@@ -99,6 +112,7 @@ hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
 hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st);       // bf16: the packed weights alone
 hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, int hints, hipStream_t st);   // calibration
+hipError_t launch_lstm_rec_quad(const LstmArgs &a, int t0, int nb, hipStream_t st);   // bf16, d_g = 512: one block of steps of the recurrence on quadruples of workgroups
 hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

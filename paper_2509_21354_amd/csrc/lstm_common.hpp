@@ -46,6 +46,23 @@ template <int DG> struct Geo {
     static constexpr int ks_of(int i) { return i % KS; }
 };
 
+// Scratch layout of the input projections: 1 KiB blocks of 64 lanes x 4 floats, one per
+// (group of 16 sequences, step of the block, wave, unit tile, gate).
+template <int DG>
+__device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, int ut, int q)
+{
+    return ((((size_t)group * tb + tt) * Geo<DG>::NW + wave) * Geo<DG>::UT + ut) * 4 + q;
+}
+
+__device__ __forceinline__ void lds_barrier()
+{
+    // LDS traffic of this wave done, then the barrier: unlike __syncthreads() this does not wait for the global
+    // stores in flight (a publication to other workgroups), which nobody in the workgroup reads
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 constexpr int kScaleBlocks = 32;   // partial maxima of |W_hh| per layer (one per preparation workgroup)
 
 // The power of two s that lifts max |W_hh| of a layer into [2^14, 2^15), from the

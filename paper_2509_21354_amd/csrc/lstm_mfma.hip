@@ -85,14 +85,6 @@ template <int DG> struct Res {
     static_assert(lds <= 160 * 1024, "LDS budget of a CU");
 };
 
-// Scratch layout: 1 KiB blocks of 64 lanes x 4 floats, one per
-// (sequence group, step of the block, wave, unit tile, gate).
-template <int DG>
-__device__ __forceinline__ size_t xp_block(int group, int tb, int tt, int wave, int ut, int q)
-{
-    return ((((size_t)group * tb + tt) * Geo<DG>::NW + wave) * Geo<DG>::UT + ut) * 4 + q;
-}
-
 // The 16 sequences x TT steps of input rows [Kbar_t ; Vbar_t] that a workgroup projects are staged once in
 // LDS (every wave needs all of them as the B operand); a wave keeps the 2d-long weight rows of one (unit tile,
 // gate) in registers and walks the TT steps with them.  Its output is the bulk of the traffic (4*d_g floats per
@@ -506,15 +498,6 @@ template <int DG> struct PairGeo {
     static constexpr size_t lds = lds_h + lds_up + 16;
 };
 
-__device__ __forceinline__ void lds_barrier()
-{
-    // LDS traffic of this wave done, then the barrier: unlike __syncthreads() this does not wait for the global
-    // stores in flight (the publication), which nobody in the workgroup reads
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 template <int DG>
 __global__ __launch_bounds__(512) void lstm_rec_pair_kernel(LstmArgs a, int t0, int nb)
 {
@@ -837,7 +820,7 @@ static hipError_t set_attributes_once()
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTT * 16 * (2 * 128 + 8) * sizeof(bf16_t)));
     if (e != hipSuccess) return e;
     if constexpr (DG == 256 || DG == 512) {
-        static_assert(PairGeo<DG>::exch_bytes == (DG / 256) * 65536, "the scratch planner's figure");
+        static_assert(PairGeo<DG>::exch_bytes == (DG / 256) * kLstmPairExchBytes256, "the scratch planner's figure");
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(lstm_rec_pair_kernel<DG>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)PairGeo<DG>::lds);
         if (e != hipSuccess) return e;
@@ -897,8 +880,15 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
             if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
             else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
         }
+        if constexpr (DG == 512) {
+            if (a.split == 4) {
+                e = launch_lstm_rec_quad(a, t0, nb, st);
+                if (e != hipSuccess) return e;
+                continue;
+            }
+        }
         if constexpr (DG == 256 || DG == 512) {
-            if (a.exch_bytes) {
+            if (a.split == 2) {
                 hipLaunchKernelGGL((lstm_rec_pair_kernel<DG>), dim3(2 * groups), dim3(512), PairGeo<DG>::lds, st, a, t0, nb);
                 continue;
             }

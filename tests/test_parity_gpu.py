@@ -250,7 +250,10 @@ LSTM_CASES = [
     _cfg(148, "bf16", d=128, T=800, C=32, d_g=256, L=1, B=2, H=24),       # 3 full groups, each on a pair of workgroups
     _cfg(149, "bf16", d=64, T=192, C=32, d_g=256, L=4, B=4, H=64),        # 64 groups: the largest paired launch
     _cfg(150, "bf16", d=64, T=192, C=32, d_g=256, L=13, B=5, H=16),       # 65 groups: one workgroup per group again
-    _cfg(152, "bf16", d=128, T=288, C=32, d_g=512, L=2, B=2, H=12),       # widest gate on pairs: 2 tiles per wave, weights streamed
+    _cfg(152, "bf16", d=128, T=288, C=32, d_g=512, L=2, B=2, H=12),       # widest gate, 24 sequences per layer: four workgroups per 32 sequences, the second block of 16 half empty
+    _cfg(153, "bf16", d=128, T=1024, C=32, d_g=512, L=1, B=2, H=16),      # one full group of 32 on four workgroups, 32 steps
+    _cfg(154, "bf16", d=64, T=256, C=32, d_g=512, L=2, B=5, H=16),        # 80 sequences per layer: the third group of 32 has one block of 16 only
+    _cfg(155, "bf16", d=128, T=160, C=32, d_g=512, L=3, B=1, H=16),       # 16 sequences per layer: stays on pairs of workgroups
 ]
 
 
@@ -343,12 +346,18 @@ def test_lstm_gate_single_kernel_form(cfg):
         assert torch.equal(x, y)
 
 
-def test_lstm_pair_wait_expires_cleanly():
-    """The paired recurrence (d_g = 256, few groups) with one member's publications withheld and a tiny bound on
-    the polls: both workgroups give up, every kernel ends normally, the launch's scores and cell state are NaN and
-    the status word at the head of the workspace is set; it stays set until the caller clears it, and the next call
-    (defaults restored) computes as usual."""
-    cfg = _cfg(151, "bf16", d=64, T=320, C=32, d_g=256, L=1, B=1, H=5)
+WAIT_CASES = [
+    _cfg(151, "bf16", d=64, T=320, C=32, d_g=256, L=1, B=1, H=5),         # a pair of workgroups
+    _cfg(156, "bf16", d=64, T=320, C=32, d_g=512, L=1, B=1, H=20),        # four workgroups per 32 sequences
+]
+
+
+@pytest.mark.parametrize("cfg", WAIT_CASES, ids=lambda c: c.name)
+def test_lstm_pair_wait_expires_cleanly(cfg):
+    """The recurrence on workgroups that exchange h every step (pairs at d_g = 256, quadruples at d_g = 512; few
+    groups) with one member's publications withheld and a tiny bound on the polls: every workgroup gives up, every
+    kernel ends normally, the launch's scores and cell state are NaN and the status word at the head of the workspace
+    is set; it stays set until the caller clears it, and the next call (defaults restored) computes as usual."""
     N = cfg.T // cfg.C
     w = synth.make_weights(cfg, "cpu")
     Kbar, Vbar = _summaries(cfg, N)
