@@ -278,7 +278,8 @@ static size_t lstm_ws_pack(const kvev_shape *sh, bool prepared)
 
 static size_t lstm_ws_per_step(const kvev_shape *sh)
 {
-    if (!lstm_takes_mfma(sh) || lstm_takes_fused(sh)) return 0;
+    // (the single-kernel forms, d_g = 256 at scale and d_g = 512 on quadruples, keep no projections in scratch)
+    if (!lstm_takes_mfma(sh) || lstm_takes_fused(sh) || lstm_split_of(sh) == 4) return 0;
     return (size_t)lstm_groups(sh) * 16 * 4 * sh->d_g * sizeof(float);
 }
 
@@ -383,7 +384,8 @@ static int lstm_gate_common(const kvev_shape *sh, const void *Kbar, const void *
         const size_t per = lstm_ws_per_step(sh), pack = lstm_ws_pack(sh, prepared);
         if (!ws || !aligned16(ws) || ws_bytes < pack + per) return KVEV_ERR_WORKSPACE;
         a.fused = lstm_takes_fused(sh) ? 1 : 0;
-        size_t tb = a.fused ? (size_t)(chunk_end - chunk_begin) : (ws_bytes - pack) / per;
+        a.split = lstm_split_of(sh);
+        size_t tb = per == 0 ? (size_t)(chunk_end - chunk_begin) : (ws_bytes - pack) / per;
         if (tb > (size_t)(chunk_end - chunk_begin)) tb = (size_t)(chunk_end - chunk_begin);
         a.tb = (int)tb;
         unsigned char *p = static_cast<unsigned char *>(ws);
@@ -396,7 +398,6 @@ static int lstm_gate_common(const kvev_shape *sh, const void *Kbar, const void *
             lstm_packed_pointers(sh, p, a);
             p += lstm_ws_weights(sh);
         }
-        a.split = lstm_split_of(sh);
         a.exch_bytes = lstm_exch_bytes(sh);
         a.exch = a.exch_bytes ? p : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);

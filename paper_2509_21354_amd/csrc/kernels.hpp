@@ -67,7 +67,7 @@ struct LstmArgs {
 // compute unit and a layer has more than 16 sequences.  Then all workgroups can be resident together on an idle
 // device (bounded waits in the kernels cover the rest).
 constexpr size_t kLstmPairExchBytes256 = 65536;     // scratch per group of 16 sequences and 256 hidden units
-constexpr size_t kLstmQuadExchBytes = 262144;       // scratch per group of 32 sequences
+constexpr size_t kLstmQuadExchBytes = 131072;       // scratch per group of 32 sequences
 inline int lstm_split(int d_g, int L, int BH, int compute_units, bool quad_allowed)
 {
     const long long g16 = (long long)L * ((BH + 15) / 16), g32 = (long long)L * ((BH + 31) / 32);
@@ -112,7 +112,7 @@ hipError_t launch_lstm_generic(const LstmArgs &a, int dtype, hipStream_t st);
 hipError_t launch_lstm_mfma(const LstmArgs &a, hipStream_t st);          // bf16
 hipError_t launch_lstm_prepare(const LstmArgs &a, hipStream_t st);       // bf16: the packed weights alone
 hipError_t launch_stream_probe(const void *src, size_t tiles, int tile_bytes, void *dst, int write_bytes, int hints, hipStream_t st);   // calibration
-hipError_t launch_lstm_rec_quad(const LstmArgs &a, int t0, int nb, hipStream_t st);   // bf16, d_g = 512: one block of steps of the recurrence on quadruples of workgroups
+hipError_t launch_lstm_quad(const LstmArgs &a, hipStream_t st);          // bf16, d_g = 512: projection and recurrence of 32 sequences on four workgroups (weights already packed)
 hipError_t launch_lstm_fused(const LstmArgs &a, hipStream_t st);         // bf16, d_g = 256: the recurrence with the input projection inside (weights already packed)
 
 }  // namespace kvev

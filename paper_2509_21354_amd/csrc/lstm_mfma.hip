@@ -865,6 +865,9 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
     if constexpr (DG == 256) {
         if (a.fused) return launch_lstm_fused(a, st);
     }
+    if constexpr (DG == 512) {
+        if (a.split == 4) return launch_lstm_quad(a, st);
+    }
     for (int t0 = a.c0; t0 < a.c1; t0 += a.tb) {
         const int nb = a.c1 - t0 < a.tb ? a.c1 - t0 : a.tb;
         // few sequences: shorter runs of steps per workgroup so that the launch still covers the chip
@@ -879,13 +882,6 @@ static hipError_t launch_dg(const LstmArgs &a, hipStream_t st)
         } else {
             if (small) hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, 2>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
             else hipLaunchKernelGGL((lstm_inproj_kernel<DG, 128, kTT>), grid_in, dim3(Geo<DG>::THREADS), lds_in, st, a, t0, nb);
-        }
-        if constexpr (DG == 512) {
-            if (a.split == 4) {
-                e = launch_lstm_rec_quad(a, t0, nb, st);
-                if (e != hipSuccess) return e;
-                continue;
-            }
         }
         if constexpr (DG == 256 || DG == 512) {
             if (a.split == 2) {
