@@ -91,6 +91,9 @@ def rec_kernel_name(cfg):
     groups = cfg.L * ((cfg.B * cfg.kv_heads + 15) // 16)
     if cfg.d_g == 256 and groups >= 257:
         return f"lstm_fused_kernel<{cfg.d}>"
+    bh = cfg.B * cfg.kv_heads
+    if cfg.d_g == 512 and bh > 16 and 4 * cfg.L * ((bh + 31) // 32) <= 256:
+        return f"lstm_quad_kernel<{cfg.d}>"
     paired = (cfg.d_g == 256 and groups <= 64) or (cfg.d_g == 512 and groups <= 128)
     return f"lstm_rec_pair_kernel<{cfg.d_g}>" if paired else f"lstm_rec_kernel<{cfg.d_g}>"
 
@@ -104,11 +107,13 @@ def recurrence_occupancy(cfg, gate_us):
     groups = cfg.L * ((cfg.B * cfg.kv_heads + 15) // 16)
     paired = rec_kernel_name(cfg).startswith("lstm_rec_pair")
     fused = rec_kernel_name(cfg).startswith("lstm_fused")
-    if fused:                      # 32 sequences per workgroup, the input projection's MFMAs inside the step
-        wgs = cfg.L * ((cfg.B * cfg.kv_heads + 31) // 32)
+    quad = rec_kernel_name(cfg).startswith("lstm_quad")
+    if fused or quad:              # 32 sequences per workgroup (or four of them), the input projection's MFMAs inside the step
+        members = 4 if quad else 1
+        wgs = members * cfg.L * ((cfg.B * cfg.kv_heads + 31) // 32)
         cus, rounds = min(256, wgs), -(-wgs // 256)
         mfma_per_group_step = 2 * (2 * (4 * cfg.d_g // 16) * (cfg.d_g // 32) + (4 * cfg.d_g // 16) * (2 * cfg.d // 32))
-        per_simd = mfma_per_group_step / 4 * rounds
+        per_simd = mfma_per_group_step / members / 4 * rounds
     else:
         cus = min(256, groups * (2 if paired else 1))
         rounds = -(-groups * (2 if paired else 1) // 256)
@@ -117,7 +122,7 @@ def recurrence_occupancy(cfg, gate_us):
     us_step = gate_us / cfg.N
     busy_us = per_simd * 16 / 2400.0
     return {"dependent_steps": cfg.N, "us_per_step": round(us_step, 3), "compute_units_occupied": cus,
-            "workgroups_per_sequence_group": 2 if paired else 1, "sequences_per_workgroup": 32 if fused else 16,
+            "workgroups_per_sequence_group": 4 if quad else 2 if paired else 1, "sequences_per_group": 32 if fused or quad else 16,
             "mfma_pipe_us_per_step_per_simd": round(busy_us, 3), "mfma_pipe_busy_frac_of_occupied_simds": round(busy_us / us_step, 3)}
 
 

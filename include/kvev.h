@@ -117,13 +117,16 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  * from the caller instead), and for most shapes fp32 input projections of a
  * block of steps: any size from one step's worth up is accepted, smaller blocks
  * mean more launches.  Launches of bf16 storage with d_g = 256 that give every
- * compute unit a group of 32 sequences run as one kernel and keep no
- * projections at all.  Calls that share a workspace must not overlap (it also
- * carries what the workgroups of one launch exchange).
+ * compute unit a group of 32 sequences, and with d_g = 512 of at most one group
+ * of 32 sequences per 4 compute units (more than 16 sequences per layer), run
+ * as one kernel and keep no projections at all.  Calls that share a workspace
+ * must not overlap (it also carries what the workgroups of one launch
+ * exchange).
  * Status word: the first int32 of the workspace.  Small launches (bf16; d_g =
  * 256 with at most one group of 16 sequences per 4 compute units of the device,
- * d_g = 512 per 2) run each group on two cooperating workgroups, which wait for
- * each other's data with a bounded number of polls.  Should the bound ever
+ * d_g = 512 per 2, or the groups of 32 above) run each group on two or four
+ * cooperating workgroups, which wait for each other's data with a bounded
+ * number of polls.  Should the bound ever
  * expire (the GPU held by other work for seconds), the launch still ends
  * normally, its util, gate and c entries are NaN, and it stores 1 in the status
  * word.  The library never clears the word: fill the workspace with zeros

@@ -14,10 +14,10 @@ extern "C" {
 #endif
 
 /* For tests of the gate's failure path.  Small launches of kvev_lstm_gate run a
- * group of sequences on two workgroups that wait for each other's data (see
- * kvev.h).  This sets, for later calls in this process, the number of polls one
- * such wait may take (default 1 << 22) and the member (0 or 1; -1 = none, the
- * default) that withholds what it would publish, so that its partner's wait
+ * group of sequences on two or four workgroups that wait for each other's data
+ * (see kvev.h).  This sets, for later calls in this process, the number of polls
+ * one such wait may take (default 1 << 22) and the member (0 or 1; -1 = none,
+ * the default) that withholds what it would publish, so that its partners' wait
  * expires: every kernel still ends normally, the affected launch's util, gate
  * and c come back NaN and the status word of its workspace is set.
  * Errors: INVALID_ARG for spin_limit < 1 or a member outside -1..1. */

@@ -13,7 +13,9 @@
 // Before them, once per set of weights: lstm_prep_kernel (W_ih into fragment
 // order, per-layer scale of W_hh) and lstm_pack_whh_kernel.  Launches with more
 // sequence groups than compute units take one kernel for both halves instead
-// (lstm_fused.hip), which shares the preparation and the helpers of this file.
+// (lstm_fused.hip), and so do launches at d_g = 512 that put 32 sequences on
+// four workgroups (lstm_quad.hip); both share the preparation and the packed
+// layouts of this file.
 //
 // Tiling (both kernels): v_mfma_f32_16x16x32_bf16 with the gate rows as the M
 // side (A operand = weight rows, read straight from global memory / L2 in
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 
 // ---- the recurrence of a 16-sequence group on a pair of compute units ----------------------------------------
 // With few sequences (config 2: 32) the chip is empty and the step time of the kernel above is what one CU can do:
-// at d_g = 256, 1.7 us of MFMA and a weight stream out of L2 on top; at d_g = 512 (config 5: 128 groups on 256 CUs)
+// at d_g = 256, 1.7 us of MFMA and a weight stream out of L2 on top; at d_g = 512
 // 13.7 us for the 2 MiB of W_hh that a CU pulls out of L2 every step.  Here two workgroups share a group: each owns
 // half of the hidden units (8 waves x 16 or 32 units, all four gates), so a step is half the matrix work, half the
 // gate nonlinearities and half the weight bytes per CU; at d_g = 256 its half of W_hh (256 KiB as fp16) sits in
@@ -468,8 +470,9 @@ __global__ __launch_bounds__(Geo<DG>::THREADS) void lstm_rec_kernel(LstmArgs a, 
 // Measured at config 2 (32 sequences, 4 workgroups): 2.1 us per step against 3.1 us for one workgroup per group;
 // the exchange is mostly hidden (the first look finds the data 60-90 % of the time), and what is left is a SIMD's
 // own serial work: 0.87 us of MFMA and 0.7 us of gate nonlinearities (quarter-rate exp2 and rcp) for its two
-// waves, plus two barriers and the LDS latency in front of each run of MFMAs.  At config 5 (256 workgroups): 13 us
-// per step against 20 us.
+// waves, plus two barriers and the LDS latency in front of each run of MFMAs.  At d_g = 512 with 256 workgroups: 13 us
+// per step against 20 us (launches with more than 16 sequences per layer go to four workgroups per 32 sequences instead:
+// lstm_quad.hip).
 //
 // Every wait is bounded: a wave that does not see its partner's data within a.pair_spin_limit polls raises a flag in
 // LDS, the workgroup leaves the step loop together after the next barrier, marks the launch's scores as NaN and sets
