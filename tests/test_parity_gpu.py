@@ -297,6 +297,53 @@ def test_lstm_gate(cfg):
     assert (util[..., N:] == 9.0).all() and (gate[..., N:] == 9.0).all()
 
 
+NAN_CASES = [
+    (_cfg(157, "bf16", d=128, T=256, C=32, d_g=512, L=1, B=1, H=40), 0),     # four workgroups per 32 sequences: h travels with a flag in a bit of its hi terms
+    (_cfg(158, "bf16", d=64, T=256, C=32, d_g=256, L=1, B=1, H=20), 0),      # pairs of workgroups
+    (_cfg(159, "bf16", d=128, T=256, C=32, d_g=256, L=1, B=1, H=40), 1),     # the single-kernel form
+    (_cfg(160, "bf16", d=128, T=256, C=32, d_g=512, L=1, B=1, H=9), 0),      # pairs at d_g = 512
+]
+
+
+@pytest.mark.parametrize("cfg,fused", NAN_CASES, ids=lambda c: getattr(c, "name", str(c)))
+def test_lstm_gate_nan_stays_in_its_sequence(cfg, fused):
+    """A NaN in one sequence's summaries (Eq. 3 has no rule for it: IEEE arithmetic carries it on) makes that
+    sequence's scores and state NaN from that step on, in the kernels as in the oracle, and touches no other
+    sequence, also where workgroups hand each other h."""
+    N = cfg.T // cfg.C
+    w = synth.make_weights(cfg, "cpu")
+    Kbar, Vbar = _summaries(cfg, N)
+    bad = [(0, 0, 3, 2), (0, 0, cfg.H - 2, 5)]                 # (layer, batch row, head, first bad step)
+    for l, b, hd, t in bad:
+        Kbar[l, b, hd, t, 7] = float("nan")
+    sh = kb.make_shape(cfg, N_cap=N)
+    lead = (cfg.L, cfg.B, cfg.H)
+    gw = dev(w)
+    h = torch.zeros(lead + (cfg.d_g,), device="cuda")
+    c = torch.zeros_like(h)
+    util = torch.zeros(lead + (N,), device="cuda")
+    gate = torch.zeros_like(util)
+    if fused:
+        kb.kvev_debug_lstm_fused_min_groups(1)
+    try:
+        ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+        kb.kvev_lstm_gate(sh, Kbar.cuda(), Vbar.cuda(), kb.lstm_weights(gw), 0, N, h, c, util, gate, ws)
+        torch.cuda.synchronize()
+    finally:
+        if fused:
+            kb.kvev_debug_lstm_fused_min_groups(0)
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
+    for got, ref, tol in ((util, ru, SCORE_TOL), (gate, rg, SCORE_TOL), (h, rh, SCORE_TOL), (c, rc, 2 * SCORE_TOL)):
+        got = got.cpu().numpy()
+        assert (np.isnan(got) == np.isnan(ref)).all()
+        ok = ~np.isnan(ref)
+        assert np.abs(got[ok] - ref[ok]).max() <= tol
+    for l, b, hd, t in bad:
+        assert np.isnan(ru[l, b, hd, t:]).all() and not np.isnan(ru[l, b, hd, :t]).any()
+    assert np.isnan(ru).sum() == sum(N - t for *_, t in bad)
+
+
 FUSED_CASES = [
     _cfg(181, "bf16", d=128, T=704, C=32, d_g=256, L=2, B=3, H=7),      # 21 sequences per layer: one ragged group of 32
     _cfg(182, "bf16", d=64, T=832, C=32, d_g=256, L=1, B=5, H=16),      # 80 sequences: 2.5 groups, head width 64
