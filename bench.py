@@ -154,7 +154,7 @@ class Bench:
         self.wK, self.wV, self.lw = wK, wV, lw
         sh, N, Tq = st.shape, cfg.N, cfg.Tq
 
-        def pool(t): kb.kvev_chunk_pool(sh, t["K"], t["V"], kb.POOL_MLP, wK, wV, 0, N, st.Kbar, st.Vbar, st.ws)
+        def pool(t): kb.kvev_chunk_pool(sh, t["K"], t["V"], kb.POOL_MLP, wK, wV, 0, N, st.Kbar, st.Vbar, st.ws_pool)
 
         # the gate's weights are static across decode steps: packed once, outside the timed region
         kb.kvev_lstm_prepare(sh, lw, st.packed)
@@ -437,7 +437,7 @@ class Bench:
         for name, mode in (("mean", kb.POOL_MEAN), ("max", kb.POOL_MAX), ("mlp_of_mean", kb.POOL_MLP),
                            ("mean_of_token_mlp", kb.POOL_TOKEN_MLP)):
             t_a = self.time_alone(lambda t, m=mode: kb.kvev_chunk_pool(sh, t["K"], t["V"], m, self.wK, self.wV, 0, N_,
-                                                                       st.Kbar, st.Vbar, st.ws), max(10, steps // 2))
+                                                                       st.Kbar, st.Vbar, st.ws_pool), max(10, steps // 2))
             e = {"us": round(t_a, 3), "hbm_GBps": round(self.cost["pool"]["bytes"] / t_a / 1e3, 1)}
             if mode == kb.POOL_TOKEN_MLP:
                 # 2*C*d*d_sum flop per chunk and side on the matrix cores, C*d_sum GELUs per chunk and side on the
@@ -477,7 +477,7 @@ def streaming_cfg4(torch, kb, synth):
     def frame(si, done):
         sh4.T = (si + 1) * c4.frame
         n4 = sh4.T // c4.C
-        kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
+        kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws_pool)
         kb.kvev_lstm_gate_prepared(sh4, s4.Kbar, s4.Vbar, lw4, s4.packed, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
         kb.kvev_select(sh4, s4.util, s4.gate, kb.SELECT_TOPK, c4.k, 0.0, s4.k_cap, s4.idx, s4.count)
         for j in range(c4.decode_per_step):
@@ -544,7 +544,7 @@ def streaming_cfg4(torch, kb, synth):
         r0 = (T4 - c4.frame) % ring_cap          # token p lives in ring row p mod ring_cap: a frame never wraps
         Kr4[..., r0:r0 + c4.frame, :] = kv4["K"][..., T4 - c4.frame:T4, :]     # stands for the model's cache write
         Vr4[..., r0:r0 + c4.frame, :] = kv4["V"][..., T4 - c4.frame:T4, :]
-        kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws)
+        kb.kvev_chunk_pool(sh4, kv4["K"], kv4["V"], kb.POOL_MLP, wK4, wV4, done, n4, s4.Kbar, s4.Vbar, s4.ws_pool)
         kb.kvev_lstm_gate_prepared(sh4, s4.Kbar, s4.Vbar, lw4, s4.packed, done, n4, s4.h, s4.c, s4.util, s4.gate, s4.ws)
         ncand = max(0, T4 - c4.W) // c4.C
         if ncand > ncand_old:
@@ -672,7 +672,7 @@ def calibrate_stream(torch, kb):
     out["dense_decode_attention_pure_read"] = {"bytes": db, "us": round(t_dense, 1), "GBps": round(db / t_dense / 1e3, 1)}
     pb = costs(cfg)["pool"]["bytes"]
     for name, mode in (("pool_mean_read_plus_3pct_write", kb.POOL_MEAN),):
-        t = t_of(lambda: kb.kvev_chunk_pool(st.shape, kv["K"], kv["V"], mode, None, None, 0, cfg.N, st.Kbar, st.Vbar, st.ws), 5)
+        t = t_of(lambda: kb.kvev_chunk_pool(st.shape, kv["K"], kv["V"], mode, None, None, 0, cfg.N, st.Kbar, st.Vbar, st.ws_pool), 5)
         out[name] = {"bytes": pb, "us": round(t, 1), "GBps": round(pb / t / 1e3, 1)}
     src = kv["K"].view(-1)
     dstc = kv["V"].view(-1)

@@ -91,8 +91,12 @@ typedef struct { const void *W_ih, *W_hh, *b_ih, *b_hh, *w_s, *b_s; } kvev_lstm_
  * storage dtype.
  *   K, V        [L,B,H,T_cap,d]   read: tokens [chunk_begin*C, chunk_end*C)
  *   Kbar, Vbar  [L,B,H,N_cap,d]   written: rows [chunk_begin, chunk_end) only
- * Needs 0 <= chunk_begin <= chunk_end <= floor(T/C) <= N_cap.  Workspace: none
- * (ws may be NULL).  Errors: INVALID_ARG for null/misaligned pointers, a bad
+ * Needs 0 <= chunk_begin <= chunk_end <= floor(T/C) <= N_cap.  Workspace:
+ * optional.  With kvev_workspace_bytes(KVEV_OP_CHUNK_POOL, ...) bytes (16-byte
+ * aligned) a large KVEV_POOL_MLP call first re-lays the MLP weights there for
+ * the matrix cores and is a few percent faster; the results are the same bits.
+ * ws may be NULL or smaller: then the weights are read as they are.  The first
+ * 256 bytes of ws are never touched.  Errors: INVALID_ARG for null/misaligned pointers, a bad
  * range, more than 2^30 (sequence, chunk) pairs in one call or more than
  * 2^31 - 1 summary rows in Kbar; UNSUPPORTED for d, dtype or pool_mode outside
  * the lists above. */

@@ -271,6 +271,7 @@ class DecodeState:
         # never lent to the gate)
         self.ws = alloc_workspace(workspace_bytes(OP_LSTM_GATE, full, self.N_cap), dev)
         self.packed = alloc_workspace(workspace_bytes(OP_LSTM_PREPARE, full, 0), dev)    # for kvev_lstm_prepare
+        self.ws_pool = alloc_workspace(workspace_bytes(OP_CHUNK_POOL, full, self.N_cap), dev)   # optional: the MLP weights re-laid
         nbytes = max(workspace_bytes(OP_GATED_ATTENTION, full, Tq, self.k_cap),
                      workspace_bytes(OP_DENSE_ATTENTION, full, Tq),
                      max(workspace_bytes(OP_GATED_ATTENTION, make_shape(cfg, T=t, T_cap=T_cap, N_cap=self.N_cap),
@@ -296,7 +297,7 @@ def cold_step(st: DecodeState, t: Dict[str, torch.Tensor], O: torch.Tensor, T: O
         sh.T = T
     N = sh.T // cfg.C
     kvev_chunk_pool(sh, t["K"], t["V"], pool_mode, mlp_weights(t, "K"), mlp_weights(t, "V"), 0, N,
-                    st.Kbar, st.Vbar, st.ws)
+                    st.Kbar, st.Vbar, st.ws_pool)
     kvev_lstm_gate(sh, st.Kbar, st.Vbar, lstm_weights(t), 0, N, st.h, st.c, st.util, st.gate, st.ws)
     kvev_select(sh, st.util, st.gate, SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)
     kvev_gated_attention(sh, t["Q"], t["Q"].shape[3], t["K"], t["V"], st.Kbar, st.Vbar, st.idx, st.count,

@@ -236,6 +236,19 @@ static int device_compute_units()
     return n;
 }
 
+// bf16 storage with a hidden width the 16x16x32 tiling divides: chunk pooling on the matrix cores
+static bool pool_takes_mfma(const kvev_shape *sh)
+{
+    return sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
+}
+// Scratch that kvev_chunk_pool can use (it works without): a 256-byte head that it never touches, so that a buffer
+// which also serves the gate keeps its status word, then the MLP weights re-laid for the matrix cores.
+constexpr size_t kPoolWsHead = 256;
+static size_t pool_ws_bytes(const kvev_shape *sh)
+{
+    return pool_takes_mfma(sh) ? kPoolWsHead + pool_pack_bytes(sh->L, sh->d, sh->d_sum) : 0;
+}
+
 static long long lstm_groups(const kvev_shape *sh)
 {
     return (long long)sh->L * ((sh->B * kv_heads(sh) + 15) / 16);
@@ -293,7 +306,6 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
                     const kvev_mlp_w *wV, int chunk_begin, int chunk_end, void *Kbar, void *Vbar, void *ws,
                     size_t ws_bytes, void *stream)
 {
-    (void)ws; (void)ws_bytes;
     int rc = check_shape(sh);
     if (rc) return rc;
     if (pool_mode < KVEV_POOL_MEAN || pool_mode > KVEV_POOL_TOKEN_MLP) return KVEV_ERR_UNSUPPORTED;
@@ -325,7 +337,10 @@ int kvev_chunk_pool(const kvev_shape *sh, const void *K, const void *V, int pool
     a.d_sum = sh->d_sum; a.c0 = chunk_begin; a.c1 = chunk_end; a.mode = pool_mode;
     a.compute_units = device_compute_units(); a.flush_shift = pool_flush_shift(pool_mode);
     // bf16 storage with a hidden width the 16x16x32 tiling divides goes to the matrix cores
-    const bool mfma = sh->dtype == KVEV_BF16 && sh->d_sum % 32 == 0 && sh->d_sum <= 512;
+    const bool mfma = pool_takes_mfma(sh);
+    // optional scratch: room for the MLP weights in fragment order, behind a head that is left alone
+    if (mfma && pool_mode == KVEV_POOL_MLP && ws && aligned16(ws) && ws_bytes >= pool_ws_bytes(sh))
+        a.wpack = static_cast<unsigned char *>(ws) + kPoolWsHead;
     hipError_t e;
     if (pool_mode == KVEV_POOL_TOKEN_MLP && mfma && sh->d_sum <= 256 && pool_token_mfma_lds(sh->d, sh->d_sum) <= 160 * 1024)
         e = launch_pool_token_mfma(a, static_cast<hipStream_t>(stream));     // W1 of both sides fits in LDS
@@ -556,6 +571,8 @@ size_t kvev_workspace_bytes(int op, const kvev_shape *sh, int n, int k_cap)
 {
     if (check_shape(sh, op != KVEV_OP_COMPACT_ATTENTION) != KVEV_OK || n < 0) return 0;
     switch (op) {
+    case KVEV_OP_CHUNK_POOL:
+        return pool_ws_bytes(sh);
     case KVEV_OP_LSTM_GATE:
     case KVEV_OP_LSTM_GATE_PREPARED: {
         const size_t per = lstm_ws_per_step(sh);

@@ -36,7 +36,13 @@ struct PoolArgs {
     int mode;
     int compute_units;    // of the device the launch goes to
     int flush_shift;      // the persistent form writes its summaries once per 2^flush_shift ticks of the 100 MHz real-time counter
+    void *wpack;          // workspace for the MLP weights in MFMA fragment order (pool_pack_bytes), or null: read as given
 };
+
+// The MLP weights of both sides re-laid per layer for the matrix cores: W1 and W2 as 1 KiB fragments (one 16-byte piece
+// per lane, in the order the kernel walks them), then the biases as fp32.
+constexpr size_t pool_pack_layer_bytes(int d, int d_sum) { return (size_t)8 * d_sum * d + (size_t)8 * (d_sum + d); }
+inline size_t pool_pack_bytes(int L, int d, int d_sum) { return (size_t)L * pool_pack_layer_bytes(d, d_sum); }
 
 struct LstmArgs {
     const void *Kbar, *Vbar;

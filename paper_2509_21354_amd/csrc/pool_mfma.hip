@@ -44,7 +44,12 @@ __device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t &hi, ui
 // plain reader: 7.3 TB/s alone, 5.7 TB/s with 3 % written back tile by tile, 6.6 TB/s with the same bytes written in
 // such synchronised bursts): the memory controllers turn the bus around for a handful of writes at a time unless the
 // writes arrive together.
-template <int D, int NW>
+//
+// PK: the MLP weights come from a.wpack, re-laid by pool_pack_kernel so that a wave-level load of a weight fragment is
+// 1 KiB of consecutive bytes.  As the caller gives them (row-major) such a load touches 16 rows, half a cache line of
+// each; a tile asks L2 for 128 KiB of weights next to its 256 KiB of raw rows, and at scale those requests cost the
+// kernel 3 % (the loads themselves 7 %: measured with the weights read from one cached fragment).
+template <int D, int NW, bool PK>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(PoolArgs a)
 {
     constexpr int RPW = 16 / NW;         // tile rows per wave
@@ -266,16 +271,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(Poo
         // ---- 2. layer 1: act = GELU(W1 xbar + b1), tiles of 16 hidden units ------
         const int ds = a.d_sum;
         const int tiles1 = ds / 16;
+        // this layer's packed weights: [W1: side, unit tile, k-step][W2: side, output tile, k-step][b1: side][b2: side]
+        const unsigned char *wpl = static_cast<const unsigned char *>(a.wpack) + (size_t)l * ((size_t)8 * ds * D + (size_t)8 * (ds + D));
         for (int t = wave; t < 2 * tiles1; t += NW) {
             const int kv = t / tiles1, u0 = (t % tiles1) * 16;
             const bf16_t *W1 = static_cast<const bf16_t *>(kv ? a.W1V : a.W1K) + ((size_t)l * ds + u0 + n) * D + g4 * 8;
             const bf16_t *b1 = static_cast<const bf16_t *>(kv ? a.b1V : a.b1K) + (size_t)l * ds + u0 + 4 * g4;
+            const bf16x8_t *W1p = reinterpret_cast<const bf16x8_t *>(wpl) + (size_t)t * (D / 32) * 64 + lane;
             f32x4_t acc;
+            if constexpr (PK) {
+                acc = *reinterpret_cast<const f32x4_t *>(wpl + (size_t)8 * ds * D + ((size_t)kv * ds + u0 + 4 * g4) * 4);
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b1[r]);
+                for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b1[r]);
+            }
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks) {
-                const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W1 + ks * 32);
+                const bf16x8_t w = PK ? W1p[ks * 64] : *reinterpret_cast<const bf16x8_t *>(W1 + ks * 32);
 #pragma unroll
                 for (int p = 2; p >= 0; --p) {
                     const bf16x8_t x = *reinterpret_cast<const bf16x8_t *>(xm + ((p * 2 + kv) * 16 + n) * XP + ks * 32 + g4 * 8);
@@ -298,11 +310,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(Poo
             const int kv = t / tiles2, e0 = (t % tiles2) * 16;
             const bf16_t *W2 = static_cast<const bf16_t *>(kv ? a.W2V : a.W2K) + ((size_t)l * D + e0 + n) * ds + g4 * 8;
             const bf16_t *b2 = static_cast<const bf16_t *>(kv ? a.b2V : a.b2K) + (size_t)l * D + e0 + 4 * g4;
+            const bf16x8_t *W2p = reinterpret_cast<const bf16x8_t *>(wpl + (size_t)4 * ds * D) + (size_t)t * (ds / 32) * 64 + lane;
             f32x4_t acc;
+            if constexpr (PK) {
+                acc = *reinterpret_cast<const f32x4_t *>(wpl + (size_t)8 * ds * D + ((size_t)2 * ds + kv * D + e0 + 4 * g4) * 4);
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b2[r]);
+                for (int r = 0; r < 4; ++r) acc[r] = bf16_to_f32(b2[r]);
+            }
             for (int ks = 0; ks < ds / 32; ++ks) {
-                const bf16x8_t w = *reinterpret_cast<const bf16x8_t *>(W2 + ks * 32);
+                const bf16x8_t w = PK ? W2p[ks * 64] : *reinterpret_cast<const bf16x8_t *>(W2 + ks * 32);
 #pragma unroll
                 for (int p = 2; p >= 0; --p) {
                     const bf16x8_t x = *reinterpret_cast<const bf16x8_t *>(act + ((size_t)(p * 2 + kv) * 16 + n) * AP + ks * 32 + g4 * 8);
@@ -325,6 +342,41 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 1) void pool_mfma_kernel(Poo
     flush();
 }
 
+// One 16-byte piece per thread: the weight fragments in the order pool_mfma_kernel<D, NW, true> reads them, then the
+// biases as fp32 (four per thread).
+template <int D>
+__global__ __launch_bounds__(256) void pool_pack_kernel(PoolArgs a)
+{
+    const int ds = a.d_sum;
+    const size_t nw = (size_t)2 * ds * D / 8;                 // pieces of W1 (both sides) per layer; W2 has as many
+    const size_t nb = (size_t)2 * (ds + D) / 4;               // bias pieces per layer
+    const size_t per_layer = 2 * nw + nb;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= per_layer * a.L) return;
+    const int l = (int)(i / per_layer);
+    size_t r = i % per_layer;
+    unsigned char *dst = static_cast<unsigned char *>(a.wpack) + (size_t)l * pool_pack_layer_bytes(D, ds) + r * 16;
+    if (r < 2 * nw) {
+        const bool second = r >= nw;                           // W2: rows are output elements, columns hidden units
+        if (second) r -= nw;
+        const int rows = second ? D : ds, cols = second ? ds : D, ksn = cols / 32;
+        const int lane = (int)(r % 64);
+        size_t q = r / 64;
+        const int ks = (int)(q % ksn); q /= ksn;
+        const int t = (int)(q % (rows / 16)), kv = (int)(q / (rows / 16));
+        const bf16_t *W = static_cast<const bf16_t *>(second ? (kv ? a.W2V : a.W2K) : (kv ? a.W1V : a.W1K));
+        const bf16_t *src = W + ((size_t)l * rows + t * 16 + (lane & 15)) * cols + ks * 32 + (lane >> 4) * 8;
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+    } else {
+        r -= 2 * nw;                                           // four biases: b1 of K, b1 of V, b2 of K, b2 of V
+        const int e = (int)r * 4;
+        const bf16_t *b;
+        if (e < 2 * ds) b = static_cast<const bf16_t *>(e < ds ? a.b1K : a.b1V) + (size_t)l * ds + e % ds;
+        else b = static_cast<const bf16_t *>(e - 2 * ds < D ? a.b2K : a.b2V) + (size_t)l * D + (e - 2 * ds) % D;
+        *reinterpret_cast<float4 *>(dst) = make_float4(bf16_to_f32(b[0]), bf16_to_f32(b[1]), bf16_to_f32(b[2]), bf16_to_f32(b[3]));
+    }
+}
+
 // Workgroups of the persistent form: as many as stay resident at once (by LDS and registers), per compute unit.  The
 // answer for the last LDS size asked about is kept (one word: size and answer together), so that a serving loop does not
 // query the runtime on every launch.
@@ -335,7 +387,7 @@ template <int D> static int persistent_grid(size_t lds, int compute_units)
     int per_cu = 0;
     if (seen != 0 && (seen >> 8) == lds) per_cu = (int)(seen & 0xff);
     else {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pool_mfma_kernel<D, 4>, 256, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pool_mfma_kernel<D, 4, true>, 256, lds) != hipSuccess || per_cu < 1) per_cu = 1;
         per_cu = std::min(per_cu, 255);
         last.store(((uint64_t)lds << 8) | (uint64_t)per_cu, std::memory_order_relaxed);
     }
@@ -350,12 +402,24 @@ hipError_t launch_pool_mfma(const PoolArgs &a, hipStream_t st)
     if (blocks == 0) return hipSuccess;
     const size_t lds = sizeof(bf16_t) * 3 * 2 * 16 * (((size_t)a.d + 8) + ((size_t)a.d_sum + 8));
     const bool few = blocks < 2048;          // fewer than 8 tiles per compute unit
+    // launches that fill the chip many times over read the MLP weights in fragment order when the caller gave room for them
+    const bool pk = !few && a.mode == KVEV_POOL_MLP && a.wpack != nullptr;
+    if (pk) {
+        const size_t pieces = pool_pack_bytes(a.L, a.d, a.d_sum) / 16;
+        const dim3 pgrid((unsigned)((pieces + 255) / 256));
+        if (a.d == 64) hipLaunchKernelGGL((pool_pack_kernel<64>), pgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((pool_pack_kernel<128>), pgrid, dim3(256), 0, st, a);
+    }
     if (a.d == 64) {
-        if (few) hipLaunchKernelGGL((pool_mfma_kernel<64, 16>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
-        else hipLaunchKernelGGL((pool_mfma_kernel<64, 4>), dim3((unsigned)std::min<size_t>(blocks, persistent_grid<64>(lds, a.compute_units))), dim3(256), lds, st, a);
+        const dim3 pgrid((unsigned)std::min<size_t>(blocks, persistent_grid<64>(lds, a.compute_units)));
+        if (few) hipLaunchKernelGGL((pool_mfma_kernel<64, 16, false>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
+        else if (pk) hipLaunchKernelGGL((pool_mfma_kernel<64, 4, true>), pgrid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((pool_mfma_kernel<64, 4, false>), pgrid, dim3(256), lds, st, a);
     } else {
-        if (few) hipLaunchKernelGGL((pool_mfma_kernel<128, 16>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
-        else hipLaunchKernelGGL((pool_mfma_kernel<128, 4>), dim3((unsigned)std::min<size_t>(blocks, persistent_grid<128>(lds, a.compute_units))), dim3(256), lds, st, a);
+        const dim3 pgrid((unsigned)std::min<size_t>(blocks, persistent_grid<128>(lds, a.compute_units)));
+        if (few) hipLaunchKernelGGL((pool_mfma_kernel<128, 16, false>), dim3((unsigned)blocks), dim3(1024), lds, st, a);
+        else if (pk) hipLaunchKernelGGL((pool_mfma_kernel<128, 4, true>), pgrid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((pool_mfma_kernel<128, 4, false>), pgrid, dim3(256), lds, st, a);
     }
     return hipGetLastError();
 }

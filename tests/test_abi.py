@@ -161,7 +161,10 @@ def test_workspace_query():
     gated = kb.workspace_bytes(kb.OP_GATED_ATTENTION, sh, 1, 32)
     assert dense > 0 and gated >= 0 and dense % 8 == 0
     assert kb.workspace_bytes(kb.OP_SELECT, sh, 1) == 0
-    assert kb.workspace_bytes(kb.OP_CHUNK_POOL, sh, 128) == 0
+    # pooling: optional room for the MLP weights re-laid (a 256-byte head + 8 d_sum d + 8 (d_sum + d) bytes per layer)
+    assert kb.workspace_bytes(kb.OP_CHUNK_POOL, sh, 128) == (256 + sh.L * (8 * sh.d_sum * sh.d + 8 * (sh.d_sum + sh.d))
+                                                             if sh.dtype == kb.BF16 and sh.d_sum % 32 == 0 else 0)
+    assert kb.workspace_bytes(kb.OP_CHUNK_POOL, kb.make_shape(synth.CONFIGS[1]), 4) == 0      # fp32 storage: nothing to re-lay
     assert kb.workspace_bytes(kb.OP_DENSE_ATTENTION, _shape(L=0), 1) == 0
     big = kb.make_shape(synth.CONFIGS[3])
     assert kb.workspace_bytes(kb.OP_GATED_ATTENTION, big, 1, 64) == 0    # 8192 sequences: no split needed

@@ -138,7 +138,7 @@ def test_config4_streaming_full_size_sampled():
         T = (s + 1) * cfg.frame
         sh.T = T
         N = T // cfg.C
-        kb.kvev_chunk_pool(sh, g["K"], g["V"], kb.POOL_MLP, wK, wV, done, N, st.Kbar, st.Vbar, st.ws)
+        kb.kvev_chunk_pool(sh, g["K"], g["V"], kb.POOL_MLP, wK, wV, done, N, st.Kbar, st.Vbar, st.ws_pool)
         kb.kvev_lstm_gate(sh, st.Kbar, st.Vbar, lw, done, N, st.h, st.c, st.util, st.gate, st.ws)
         done = N
         kb.kvev_select(sh, st.util, st.gate, kb.SELECT_TOPK, cfg.k, 0.0, st.k_cap, st.idx, st.count)

@@ -223,6 +223,16 @@ def test_chunk_pool(cfg, mode):
     wK, wV = kb.mlp_weights(g, "K"), kb.mlp_weights(g, "V")
     kb.kvev_chunk_pool(sh, g["K"], g["V"], mode, wK, wV, c0, c1, Kbar, Vbar)
     torch.cuda.synchronize()
+    if mode == kb.POOL_MLP:
+        # with the optional scratch (large launches re-lay the MLP weights in it first): the same bits, and the
+        # head of the scratch and everything behind the size asked for stay as they were
+        nws = kb.workspace_bytes(kb.OP_CHUNK_POOL, sh, c1 - c0)
+        ws = torch.full((nws + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+        K2, V2 = torch.full_like(Kbar, 3.0), torch.full_like(Vbar, 3.0)
+        kb.kvev_chunk_pool(sh, g["K"], g["V"], mode, wK, wV, c0, c1, K2, V2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(K2, Kbar) and torch.equal(V2, Vbar)
+        assert (ws[:256] == 0x5A).all() and (ws[nws:] == 0x5A).all()
     rK, rV = orc.chunk_pool(t["K"], t["V"], cfg.T, cfg.C, N_cap, cfg.d_sum, mode,
                             kb.mlp_weights(t, "K"), kb.mlp_weights(t, "V"), c0, c1)
     assert_close_storage(Kbar[..., c0:c1, :], rK[..., c0:c1, :], cfg.dtype, "Kbar")
