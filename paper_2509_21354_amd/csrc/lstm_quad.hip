@@ -93,9 +93,18 @@ __global__ __launch_bounds__(512) void lstm_quad_kernel(LstmArgs a, int t0, int 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g4 = lane >> 4;
-    const int member = blockIdx.x & 3, gid = blockIdx.x >> 2;
     const int gpl = (a.BH + SEQ - 1) / SEQ;
-    if (gid >= a.L * gpl) return;
+    // Members of a group are neighbours in the launch order, and hardware workgroup ids go round-robin over the 8
+    // XCDs: XCD x runs member x % 4 of the groups of the parity of x / 4.  The groups of one parity are given a
+    // contiguous run of (layer, group) pairs, so that an XCD's L2 serves one member's weights of half the layers, and
+    // the groups of a layer find them there together, instead of every layer's weights once.
+    const int member = blockIdx.x & 3;
+    int gid = blockIdx.x >> 2;
+    {
+        const int ng = a.L * gpl;
+        if (gid >= ng) return;
+        if (ng % 2 == 0) gid = (gid & 1) * (ng / 2) + (gid >> 1);
+    }
     const int l = gid / gpl, grp = gid % gpl;
     bool live[SB];
     size_t sq[SB];
