@@ -168,6 +168,15 @@ def test_workspace_query():
     assert kb.workspace_bytes(kb.OP_DENSE_ATTENTION, _shape(L=0), 1) == 0
     big = kb.make_shape(synth.CONFIGS[3])
     assert kb.workspace_bytes(kb.OP_GATED_ATTENTION, big, 1, 64) == 0    # 8192 sequences: no split needed
+    # the gate's scratch: forms that run as one kernel keep no projections, so the block length does not matter
+    # (config 3: d_g = 256, a group of 32 sequences per compute unit; config 5: d_g = 512, four workgroups per 32
+    # sequences, whose exchange slots take 128 KiB per group), the two-kernel form grows with it (config 2)
+    for cfg, groups32 in ((synth.CONFIGS[3], 0), (synth.CONFIGS[5], 32 * 2)):
+        g = kb.make_shape(cfg)
+        one, many = kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, g, 1), kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, g, 128)
+        assert one == many == 256 + groups32 * 131072
+    small = kb.make_shape(synth.CONFIGS[2])
+    assert kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, small, 8) > kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, small, 1) > 0
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
