@@ -204,6 +204,7 @@ POOL_CASES = [
     # their summaries back until the next write slot), full and ragged
     _cfg(129, "bf16", d=128, T=1026, C=2, d_sum=128, L=1, B=4, H=16),
     _cfg(130, "bf16", d=64, T=2052, C=4, d_sum=64, L=1, B=5, H=13),
+    _cfg(128, "bf16", d=64, T=1026, C=2, d_sum=96, L=2, B=2, H=16),       # two layers, three k-steps in the second MLP layer
 ]
 
 
