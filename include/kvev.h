@@ -121,9 +121,9 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  * from the caller instead), and for most shapes fp32 input projections of a
  * block of steps: any size from one step's worth up is accepted, smaller blocks
  * mean more launches.  Launches of bf16 storage with d_g = 256 that give every
- * compute unit a group of 32 sequences, and with d_g = 512 of at most one group
- * of 32 sequences per 4 compute units (more than 16 sequences per layer), run
- * as one kernel and keep no projections at all.  Calls that share a workspace
+ * compute unit a group of 32 sequences, and with d_g = 512 and more than 16
+ * sequences per layer, run as one kernel (at d_g = 512 once per compute
+ * units / 4 groups of 32 sequences) and keep no projections at all.  Calls that share a workspace
  * must not overlap (it also carries what the workgroups of one launch
  * exchange).
  * Status word: the first int32 of the workspace.  Small launches (bf16; d_g =

@@ -30,6 +30,13 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member);
  * default.  Errors: INVALID_ARG for a negative value. */
 int kvev_debug_lstm_fused_min_groups(int min_groups);
 
+/* For parity tests of large calls of the gate at d_g = 512, which the library cuts into launches of at most one
+ * workgroup per compute unit (four workgroups per group of 32 sequences).  This lowers the number of groups per
+ * launch for later calls in this process (and the exchange scratch that kvev_workspace_bytes reports with it), so
+ * that a shape the CPU oracle finishes in seconds takes several launches; 0 restores the default (compute units / 4).
+ * Errors: INVALID_ARG for a negative value. */
+int kvev_debug_lstm_quad_groups(int groups);
+
 /* The single-query attention kernels read their rows with the non-temporal hint
  * when a launch reads more than `bytes` (default 256 MiB, what the memory-side
  * cache holds; 0 restores the default).  Lowering it to 1 lets a parity test run

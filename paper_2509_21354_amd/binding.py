@@ -29,7 +29,7 @@ OP_LSTM_PREPARE, OP_LSTM_GATE_PREPARED = 6, 7
 EXPORTS = ("kvev_chunk_pool", "kvev_lstm_gate", "kvev_lstm_prepare", "kvev_lstm_gate_prepared", "kvev_select", "kvev_gated_attention",
            "kvev_gated_attention_static", "kvev_dense_attention", "kvev_retain", "kvev_compact_attention", "kvev_workspace_bytes",
            "kvev_status_string", "kvev_last_hip_error", "kvev_version")
-TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups", "kvev_debug_stream_probe",
+TEST_HOOKS = ("kvev_debug_pair_wait", "kvev_debug_lstm_fused_min_groups", "kvev_debug_lstm_quad_groups", "kvev_debug_stream_probe",
               "kvev_debug_attn_stream_bytes")      # include/kvev_test_hooks.h
 
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.kvev_debug_attn_stream_bytes.restype = ci
         L.kvev_debug_lstm_fused_min_groups.argtypes = [ci]
         L.kvev_debug_lstm_fused_min_groups.restype = ci
+        L.kvev_debug_lstm_quad_groups.argtypes = [ci]
+        L.kvev_debug_lstm_quad_groups.restype = ci
         L.kvev_debug_stream_probe.argtypes = [vp, sz, ci, vp, sz, ci, ci, vp]
         L.kvev_debug_stream_probe.restype = ci
         L.kvev_status_string.argtypes = [ci]
@@ -145,6 +147,10 @@ def kvev_debug_pair_wait(spin_limit: int = 1 << 22, mute_member: int = -1) -> No
 
 def kvev_debug_attn_stream_bytes(nbytes: int = 0) -> None:
     _check(lib().kvev_debug_attn_stream_bytes(nbytes), "kvev_debug_attn_stream_bytes")
+
+
+def kvev_debug_lstm_quad_groups(groups: int = 0) -> None:
+    _check(lib().kvev_debug_lstm_quad_groups(groups), "kvev_debug_lstm_quad_groups")
 
 
 def kvev_debug_lstm_fused_min_groups(min_groups: int = 0) -> None:

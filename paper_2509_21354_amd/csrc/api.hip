@@ -280,9 +280,17 @@ static int lstm_split_of(const kvev_shape *sh)
 {
     return lstm_takes_fused(sh) ? 0 : lstm_split(sh->d_g, sh->L, sh->B * kv_heads(sh), device_compute_units(), g_lstm_quad != 0);
 }
+// groups of 32 sequences that one launch of the four-workgroup kernel takes: a workgroup per compute unit at most
+// (kvev_debug_lstm_quad_groups lowers it, so that a small shape walks the several-launches path)
+static std::atomic<int> g_lstm_quad_groups{0};
+static int lstm_quad_groups()
+{
+    const int forced = g_lstm_quad_groups.load(), fit = device_compute_units() / 4;
+    return forced > 0 && forced < fit ? forced : (fit > 0 ? fit : 1);
+}
 static size_t lstm_exch_bytes(const kvev_shape *sh)
 {
-    return lstm_split_exch_bytes(lstm_split_of(sh), sh->d_g, sh->L, sh->B * kv_heads(sh));
+    return lstm_split_exch_bytes(lstm_split_of(sh), sh->d_g, sh->L, sh->B * kv_heads(sh), lstm_quad_groups());
 }
 static size_t lstm_ws_pack(const kvev_shape *sh, bool prepared)
 {
@@ -414,6 +422,7 @@ static int lstm_gate_common(const kvev_shape *sh, const void *Kbar, const void *
             p += lstm_ws_weights(sh);
         }
         a.exch_bytes = lstm_exch_bytes(sh);
+        a.quad_groups = lstm_quad_groups();
         a.exch = a.exch_bytes ? p : nullptr;
         a.xproj = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pack);
         a.pair_spin_limit = g_pair_spin_limit.load();
@@ -542,6 +551,13 @@ int kvev_debug_pair_wait(int spin_limit, int mute_member)
 int kvev_debug_attn_stream_bytes(size_t bytes)
 {
     g_stream_bytes = bytes == 0 ? kStreamBytesDefault : bytes;
+    return KVEV_OK;
+}
+
+int kvev_debug_lstm_quad_groups(int groups)
+{
+    if (groups < 0) return KVEV_ERR_INVALID_ARG;
+    g_lstm_quad_groups = groups;
     return KVEV_OK;
 }
 

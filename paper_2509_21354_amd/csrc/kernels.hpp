@@ -55,6 +55,7 @@ struct LstmArgs {
     unsigned char *exch;  // workspace: exchange slots of the split recurrence (lstm_split_exch_bytes), or null
     size_t exch_bytes;    // 0: one workgroup per sequence group
     int split;            // workgroups that share a sequence group in the recurrence: 0 (one), 2 or 4 (lstm_split)
+    int quad_groups;      // split == 4: groups of 32 sequences per launch at most (compute units / 4)
     int pair_spin_limit;  // polls a wave of the paired recurrence spends on one wait before it gives up
     int pair_mute;        // member (0, 1) whose publications are withheld, -1: none (failure-path tests only)
     int32_t *status;      // workspace: word that a launch sets to 1 when a bounded wait expired (never cleared by the library)
@@ -76,15 +77,18 @@ constexpr size_t kLstmPairExchBytes256 = 65536;     // scratch per group of 16 s
 constexpr size_t kLstmQuadExchBytes = 131072;       // scratch per group of 32 sequences
 inline int lstm_split(int d_g, int L, int BH, int compute_units, bool quad_allowed)
 {
-    const long long g16 = (long long)L * ((BH + 15) / 16), g32 = (long long)L * ((BH + 31) / 32);
-    if (d_g == 512 && quad_allowed && BH > 16 && 4 * g32 <= compute_units) return 4;
+    const long long g16 = (long long)L * ((BH + 15) / 16);
+    if (d_g == 512 && quad_allowed && BH > 16 && compute_units >= 4) return 4;     // (more groups than fit at once: several launches)
     if (d_g == 256 && 4 * g16 <= compute_units) return 2;
     if (d_g == 512 && 2 * g16 <= compute_units) return 2;
     return 0;
 }
-inline size_t lstm_split_exch_bytes(int split, int d_g, int L, int BH)
+inline size_t lstm_split_exch_bytes(int split, int d_g, int L, int BH, int quad_groups)
 {
-    if (split == 4) return (size_t)L * ((BH + 31) / 32) * kLstmQuadExchBytes;
+    if (split == 4) {       // the slots of one launch (quad_groups groups at most), used again by the next
+        const long long g32 = (long long)L * ((BH + 31) / 32);
+        return (size_t)(g32 < quad_groups ? g32 : quad_groups) * kLstmQuadExchBytes;
+    }
     if (split == 2) return (size_t)L * ((BH + 15) / 16) * (d_g / 256) * kLstmPairExchBytes256;
     return 0;
 }

@@ -74,8 +74,9 @@ __global__ __launch_bounds__(256) void lstm_quad_clear_kernel(uint4 *p, size_t n
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
+// g0, ng: the launch takes groups g0 .. g0 + ng - 1 of the call (four workgroups each)
 template <int D>
-__global__ __launch_bounds__(512) void lstm_quad_kernel(LstmArgs a, int t0, int nb)
+__global__ __launch_bounds__(512) void lstm_quad_kernel(LstmArgs a, int t0, int nb, int g0, int ng)
 {
     using G = Geo<512>;                    // the packed operands keep the single-workgroup kernel's geometry
     using Q = QuadGeo<D>;
@@ -99,12 +100,9 @@ __global__ __launch_bounds__(512) void lstm_quad_kernel(LstmArgs a, int t0, int 
     // contiguous run of (layer, group) pairs, so that an XCD's L2 serves one member's weights of half the layers, and
     // the groups of a layer find them there together, instead of every layer's weights once.
     const int member = blockIdx.x & 3;
-    int gid = blockIdx.x >> 2;
-    {
-        const int ng = a.L * gpl;
-        if (gid >= ng) return;
-        if (ng % 2 == 0) gid = (gid & 1) * (ng / 2) + (gid >> 1);
-    }
+    const int slot = blockIdx.x >> 2;          // the group's place in this launch: its exchange slots
+    if (slot >= ng) return;
+    const int gid = g0 + (ng % 2 == 0 ? (slot & 1) * (ng / 2) + (slot >> 1) : slot);
     const int l = gid / gpl, grp = gid % gpl;
     bool live[SB];
     size_t sq[SB];
@@ -152,7 +150,7 @@ __global__ __launch_bounds__(512) void lstm_quad_kernel(LstmArgs a, int t0, int 
     };
     static_for<PF>([&](auto ic) { load_w(std::integral_constant<int, KS + decltype(ic)::value>{}); });
 
-    const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)gid * Q::exch_bytes, Q::exch_bytes);
+    const __amdgpu_buffer_rsrc_t e_rsrc = make_rsrc(a.exch + (size_t)slot * Q::exch_bytes, Q::exch_bytes);
 
     float c_reg[SB][4];
     f16_t *h_wr[NM];             // + (plane*SEQ + sb*16)*HP
@@ -452,14 +450,21 @@ static hipError_t launch_quad_d(const LstmArgs &a, hipStream_t st)
         if (e != hipSuccess) return e;
         done.fetch_or(bit, std::memory_order_release);
     }
-    const unsigned groups = (unsigned)(a.L * ((a.BH + QuadGeo<D>::SEQ - 1) / QuadGeo<D>::SEQ));
-    const size_t n16 = a.exch_bytes / 16;
-    hipLaunchKernelGGL(lstm_quad_clear_kernel, dim3((unsigned)((n16 + 1023) / 1024)), dim3(256), 0, st, reinterpret_cast<uint4 *>(a.exch), n16);
-    hipLaunchKernelGGL(lstm_quad_kernel<D>, dim3(QuadGeo<D>::NM * groups), dim3(512), QuadGeo<D>::lds, st, a, a.c0, a.c1 - a.c0);
+    const int groups = a.L * ((a.BH + QuadGeo<D>::SEQ - 1) / QuadGeo<D>::SEQ);
+    const int per_launch = a.quad_groups > 0 ? a.quad_groups : 1;
+    // at most one workgroup per compute unit at a time: a call with more groups takes several launches, one after
+    // the other on the stream, each with cleared exchange slots
+    for (int g0 = 0; g0 < groups; g0 += per_launch) {
+        const int ng = groups - g0 < per_launch ? groups - g0 : per_launch;
+        const size_t n16 = (size_t)ng * QuadGeo<D>::exch_bytes / 16;
+        hipLaunchKernelGGL(lstm_quad_clear_kernel, dim3((unsigned)((n16 + 1023) / 1024)), dim3(256), 0, st, reinterpret_cast<uint4 *>(a.exch), n16);
+        hipLaunchKernelGGL(lstm_quad_kernel<D>, dim3((unsigned)(QuadGeo<D>::NM * ng)), dim3(512), QuadGeo<D>::lds, st, a, a.c0, a.c1 - a.c0, g0, ng);
+    }
     return hipGetLastError();
 }
 
-// One launch for the whole range of steps (weights already packed), after a small one that clears the exchange slots.
+// The whole range of steps in one launch per quad_groups groups (weights already packed), each after a small launch
+// that clears the exchange slots.
 hipError_t launch_lstm_quad(const LstmArgs &a, hipStream_t st)
 {
     return a.d == 64 ? launch_quad_d<64>(a, st) : launch_quad_d<128>(a, st);

@@ -39,6 +39,7 @@ def test_debug_pair_wait_validation():
     assert L.kvev_debug_pair_wait(16, -2) == kb.ERR_INVALID_ARG
     assert L.kvev_debug_pair_wait(1 << 22, -1) == kb.OK      # the defaults
     assert L.kvev_debug_lstm_fused_min_groups(-1) == kb.ERR_INVALID_ARG
+    assert L.kvev_debug_lstm_quad_groups(-1) == kb.ERR_INVALID_ARG
     big = kb.make_shape(synth.CONFIGS[3])
     small = kb.make_shape(synth.CONFIGS[2])
     w_small = kb.workspace_bytes(kb.OP_LSTM_GATE, small, 128)
@@ -156,6 +157,7 @@ def test_pointer_range_and_mode_validation():
 
 
 def test_workspace_query():
+    L_ = kb.lib()
     sh = _shape()
     dense = kb.workspace_bytes(kb.OP_DENSE_ATTENTION, sh, 1)
     gated = kb.workspace_bytes(kb.OP_GATED_ATTENTION, sh, 1, 32)
@@ -175,6 +177,14 @@ def test_workspace_query():
         g = kb.make_shape(cfg)
         one, many = kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, g, 1), kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, g, 128)
         assert one == many == 256 + groups32 * 131072
+    # a d_g = 512 call with more groups than fit at once runs as several launches that share the slots of one
+    huge = kb.make_shape(synth.CONFIGS[5], B=256)        # 256 groups of 32 sequences
+    assert kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, huge, 512) == 256 + 64 * 131072
+    assert L_.kvev_debug_lstm_quad_groups(3) == kb.OK
+    try:
+        assert kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, huge, 512) == 256 + 3 * 131072
+    finally:
+        assert L_.kvev_debug_lstm_quad_groups(0) == kb.OK
     small = kb.make_shape(synth.CONFIGS[2])
     assert kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, small, 8) > kb.workspace_bytes(kb.OP_LSTM_GATE_PREPARED, small, 1) > 0
 

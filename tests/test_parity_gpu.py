@@ -355,6 +355,41 @@ def test_lstm_gate_nan_stays_in_its_sequence(cfg, fused):
     assert np.isnan(ru).sum() == sum(N - t for *_, t in bad)
 
 
+def test_lstm_gate_d512_in_several_launches():
+    """A d_g = 512 call with more groups of 32 sequences than the chip takes at once runs as several launches of the
+    four-workgroup kernel that share one launch's exchange slots (Eq. 3 per sequence: the cut changes no bit).  The
+    number of groups per launch is lowered so that 7 groups take 3 launches (3 + 3 + 1)."""
+    cfg = _cfg(161, "bf16", d=128, T=192, C=32, d_g=512, L=1, B=7, H=32)
+    N = cfg.T // cfg.C
+    w = synth.make_weights(cfg, "cpu")
+    Kbar, Vbar = _summaries(cfg, N)
+    sh = kb.make_shape(cfg, N_cap=N)
+    lead = (cfg.L, cfg.B, cfg.H)
+    gw = dev(w)
+    Kb, Vb = Kbar.cuda(), Vbar.cuda()
+    outs = []
+    for per_launch in (0, 3):
+        kb.kvev_debug_lstm_quad_groups(per_launch)
+        try:
+            ws = kb.alloc_workspace(kb.workspace_bytes(kb.OP_LSTM_GATE, sh, N))
+            h = torch.zeros(lead + (cfg.d_g,), device="cuda")
+            c = torch.zeros_like(h)
+            util = torch.zeros(lead + (N,), device="cuda")
+            gate = torch.zeros_like(util)
+            kb.kvev_lstm_gate(sh, Kb, Vb, kb.lstm_weights(gw), 0, N, h, c, util, gate, ws)
+            torch.cuda.synchronize()
+            assert int(ws[:4].view(torch.int32).item()) == 0
+        finally:
+            kb.kvev_debug_lstm_quad_groups(0)
+        outs.append((h, c, util, gate))
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+    rh, rc, ru, rg = orc.lstm_gate(Kbar, Vbar, kb.lstm_weights(w), 0, N)
+    assert np.abs(outs[1][2].cpu().numpy() - ru).max() <= SCORE_TOL
+    assert np.abs(outs[1][0].cpu().numpy() - rh).max() <= SCORE_TOL
+    assert np.abs(outs[1][1].cpu().numpy() - rc).max() <= 2 * SCORE_TOL
+
+
 FUSED_CASES = [
     _cfg(181, "bf16", d=128, T=704, C=32, d_g=256, L=2, B=3, H=7),      # 21 sequences per layer: one ragged group of 32
     _cfg(182, "bf16", d=64, T=832, C=32, d_g=256, L=1, B=5, H=16),      # 80 sequences: 2.5 groups, head width 64
