@@ -94,7 +94,7 @@ def rec_kernel_name(cfg):
     bh = cfg.B * cfg.kv_heads
     if cfg.d_g == 512 and bh > 16:      # (more groups than fit at once: several launches of the same kernel)
         return f"lstm_quad_kernel<{cfg.d}>"
-    paired = (cfg.d_g == 256 and groups <= 64) or (cfg.d_g == 512 and groups <= 128)
+    paired = cfg.d_g in (256, 512) and groups <= 128
     return f"lstm_rec_pair_kernel<{cfg.d_g}>" if paired else f"lstm_rec_kernel<{cfg.d_g}>"
 
 

@@ -127,8 +127,8 @@ int kvev_chunk_pool(const kvev_shape *shape, const void *K, const void *V, int p
  * must not overlap (it also carries what the workgroups of one launch
  * exchange).
  * Status word: the first int32 of the workspace.  Small launches (bf16; d_g =
- * 256 with at most one group of 16 sequences per 4 compute units of the device,
- * d_g = 512 per 2, or the groups of 32 above) run each group on two or four
+ * 256 or 512 with at most one group of 16 sequences per 2 compute units of the
+ * device, or the groups of 32 at d_g = 512 above) run each group on two or four
  * cooperating workgroups, which wait for each other's data with a bounded
  * number of polls.  Should the bound ever
  * expire (the GPU held by other work for seconds), the launch still ends

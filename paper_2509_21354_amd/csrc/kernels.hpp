@@ -66,21 +66,20 @@ struct LstmArgs {
     int fused;            // 1: the single-kernel form (d_g = 256, 32 sequences per workgroup, no projections in scratch)
 };
 
-// How the two-kernel gate spreads a group of sequences over workgroups that exchange h every step (0: one workgroup
-// per 16 sequences, no exchange).  Pairs: 16 sequences on two workgroups when the launch has at most one workgroup
-// per two compute units at d_g = 256, per compute unit at d_g = 512 (where a single workgroup is bound by the weight
-// stream out of L2 and a pair halves it).  Quadruples: at d_g = 512, 32 sequences on four workgroups (a quarter of
-// the stream each, and every fragment serves two blocks of sequences) when that is at most one workgroup per
-// compute unit and a layer has more than 16 sequences.  Then all workgroups can be resident together on an idle
-// device (bounded waits in the kernels cover the rest).
+// How the gate spreads a group of sequences over workgroups that exchange h every step (0: one workgroup per 16
+// sequences, no exchange).  Pairs: 16 sequences on two workgroups when the launch has at most one workgroup per compute
+// unit (at d_g = 512 a single workgroup is bound by the weight stream out of L2 and a pair halves it; at d_g = 256 a
+// pair keeps all of W_hh in registers).  Quadruples: at d_g = 512 with more than 16 sequences per layer, 32 sequences
+// on four workgroups (a quarter of the stream each, and every fragment serves two blocks of sequences); a launch
+// takes at most one workgroup per compute unit, larger calls are cut into several launches.  So all workgroups of a
+// launch can be resident together on an idle device (bounded waits in the kernels cover the rest).
 constexpr size_t kLstmPairExchBytes256 = 65536;     // scratch per group of 16 sequences and 256 hidden units
 constexpr size_t kLstmQuadExchBytes = 131072;       // scratch per group of 32 sequences
 inline int lstm_split(int d_g, int L, int BH, int compute_units, bool quad_allowed)
 {
     const long long g16 = (long long)L * ((BH + 15) / 16);
     if (d_g == 512 && quad_allowed && BH > 16 && compute_units >= 4) return 4;     // (more groups than fit at once: several launches)
-    if (d_g == 256 && 4 * g16 <= compute_units) return 2;
-    if (d_g == 512 && 2 * g16 <= compute_units) return 2;
+    if ((d_g == 256 || d_g == 512) && 2 * g16 <= compute_units) return 2;
     return 0;
 }
 inline size_t lstm_split_exch_bytes(int split, int d_g, int L, int BH, int quad_groups)

@@ -259,8 +259,8 @@ LSTM_CASES = [
     _cfg(146, "bf16", d=128, T=768, C=32, d_g=512, L=1, B=1, H=3),        # widest gate: unit tiles one after the other
     _cfg(147, "bf16", d=64, T=576, C=16, d_g=128, L=2, B=2, H=9),         # W_hh fully resident on chip
     _cfg(148, "bf16", d=128, T=800, C=32, d_g=256, L=1, B=2, H=24),       # 3 full groups, each on a pair of workgroups
-    _cfg(149, "bf16", d=64, T=192, C=32, d_g=256, L=4, B=4, H=64),        # 64 groups: the largest paired launch
-    _cfg(150, "bf16", d=64, T=192, C=32, d_g=256, L=13, B=5, H=16),       # 65 groups: one workgroup per group again
+    _cfg(149, "bf16", d=64, T=192, C=32, d_g=256, L=8, B=4, H=64),        # 128 groups: the largest paired launch (a workgroup per compute unit)
+    _cfg(150, "bf16", d=64, T=192, C=32, d_g=256, L=26, B=5, H=16),       # 130 groups: one workgroup per group again
     _cfg(152, "bf16", d=128, T=288, C=32, d_g=512, L=2, B=2, H=12),       # widest gate, 24 sequences per layer: four workgroups per 32 sequences, the second block of 16 half empty
     _cfg(153, "bf16", d=128, T=1024, C=32, d_g=512, L=1, B=2, H=16),      # one full group of 32 on four workgroups, 32 steps
     _cfg(154, "bf16", d=64, T=256, C=32, d_g=512, L=2, B=5, H=16),        # 80 sequences per layer: the third group of 32 has one block of 16 only
@@ -494,7 +494,7 @@ def test_lstm_pair_wait_expires_cleanly(cfg):
 
 PREPARED_CASES = [
     (_cfg(191, "bf16", d=128, T=384, C=32, d_g=256, L=1, B=1, H=20), 0),     # pairs of workgroups
-    (_cfg(192, "bf16", d=64, T=256, C=32, d_g=256, L=13, B=5, H=16), 0),     # one workgroup per group
+    (_cfg(192, "bf16", d=64, T=256, C=32, d_g=256, L=26, B=5, H=16), 0),     # one workgroup per group
     (_cfg(193, "bf16", d=128, T=256, C=32, d_g=256, L=2, B=2, H=20), 1),     # the single-kernel form
     (_cfg(194, "bf16", d=64, T=320, C=32, d_g=128, L=2, B=1, H=9), 0),       # all of W_hh in LDS
     (_cfg(195, "bf16", d=128, T=256, C=32, d_g=512, L=1, B=1, H=18), 0),     # widest gate, on pairs
